@@ -1,0 +1,148 @@
+/*
+ * libsparseloco -- the SparseLoCo outer step on one MI355X (gfx950).
+ *
+ * C ABI.  Three operations, one per group of lines of the update equations in
+ * section 2.1 of the paper ("Background: SparseLoCo", equations labelled
+ * sparse_update), run over every parameter tensor of a replica:
+ *
+ *   sparseloco_compress      delta = theta_outer - theta_local
+ *                            e     = beta * e + delta
+ *                            hat   = Q(Top-kappa per chunk of e)
+ *                            e     = e - hat
+ *   sparseloco_aggregate     delta_bar = (1/M) * sum_m hat_m
+ *   sparseloco_outer_update  theta_outer = theta_outer - eta * delta_bar
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  Arguments of
+ *     type `T* const*` are HOST arrays of device pointers (one per tensor, or
+ *     one per replica); the library copies them during the call, so the host
+ *     arrays may be reused as soon as the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; no call synchronises the device.  A call may
+ *     block on the host only to recycle one of the plan's staging slots, i.e.
+ *     to wait for work that this plan enqueued 32 calls earlier.
+ *   - A plan may be used from one host thread at a time and belongs to the
+ *     device that was current when it was created.
+ *   - Every function returns SPLC_OK or a negative status; nothing aborts or
+ *     throws.  Arguments are validated on the host before anything is enqueued.
+ *   - fp32 arithmetic is IEEE-754 round-to-nearest, one rounding per operation
+ *     (no fused multiply-add), denormals kept.  Inputs must be finite.
+ *   - A tensor is its row-major flattening; chunk = SPLC_CHUNK consecutive
+ *     elements; the last chunk of a tensor may be shorter and keeps
+ *     min(kappa, n_c) entries.  Chunks are numbered tensor by tensor in the
+ *     order given to sparseloco_plan_create.  Magnitude ties go to the lower
+ *     index.
+ *
+ * Message layout (per replica)
+ *   pairs  uint16[n_chunks * kappa]   pairs[c*kappa + t] = index | code << 12,
+ *                                     ascending index inside a chunk, index in
+ *                                     bits 0-11, code in bits 12-13 (bit 13 =
+ *                                     sign, bit 12 = upper level), bits 14-15
+ *                                     zero; unused slots (t >= kappa_c) 0xFFFF.
+ *   SPLC_QUANT_2BIT: scales float[n_chunks * 2], scales[2c] = lo, [2c+1] = hi;
+ *                    a code decodes to (sign ? -1 : +1) * (upper ? hi : lo).
+ *   SPLC_QUANT_NONE: values float[n_chunks * kappa], values[c*kappa + t] = the
+ *                    selected fp32 value itself (code bits zero); unused slots +0.
+ */
+#ifndef SPARSELOCO_H
+#define SPARSELOCO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPLC_CHUNK 4096          /* 64 x 64: chunk size of the paper's experiments (section 3, appendix table) */
+
+enum {
+    SPLC_OK = 0,
+    SPLC_EINVAL = -1,            /* bad argument (NULL, size, range, mode) */
+    SPLC_EALIGN = -2,            /* a tensor pointer is not 16-byte aligned (8-byte for bf16 sources) */
+    SPLC_ENOMEM = -3,            /* host or device allocation failed */
+    SPLC_EHIP = -4,              /* a HIP runtime call failed */
+    SPLC_EPLAN = -5              /* call does not match the plan (quantiser mode, device) */
+};
+
+enum { SPLC_F32 = 0, SPLC_BF16 = 1 };
+
+enum {
+    SPLC_DELTA_FROM_PARAMS = 0,  /* delta = theta_outer - theta_local, both given (fp32) */
+    SPLC_DELTA_DIRECT = 1        /* delta given directly, fp32 or bf16 (widened exactly) */
+};
+
+enum {
+    SPLC_QUANT_NONE = 0,         /* Q = identity: the setting of the paper's experiments */
+    SPLC_QUANT_2BIT = 1          /* sign + one magnitude bit, two levels per chunk */
+};
+
+enum {
+    SPLC_SELECT_AUTO = 0,        /* candidate filter + exact ranking, radix select when it does not apply */
+    SPLC_SELECT_RADIX = 1        /* always the radix select (same result; for tests and comparison) */
+};
+
+typedef struct sparseloco_plan sparseloco_plan;
+
+/*
+ * Build a plan for a list of tensors: the per-chunk table in device memory and
+ * the staging slots for pointer tables.  numel[i] >= 0 (empty tensors have no
+ * chunk).  kappa in 1..SPLC_CHUNK (Top-kappa per chunk, section 2.1; 32 in the
+ * paper's runs).  quant_mode: SPLC_QUANT_*.  The plan owns only what it
+ * allocates here; sparseloco_plan_destroy frees it after synchronising the
+ * device work that still uses it.
+ */
+int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel,
+                           int kappa, int quant_mode);
+void sparseloco_plan_destroy(sparseloco_plan* plan);
+
+int64_t sparseloco_plan_num_chunks(const sparseloco_plan* plan);   /* sum over tensors of ceil(numel / SPLC_CHUNK) */
+int64_t sparseloco_plan_num_params(const sparseloco_plan* plan);   /* sum of numel */
+int sparseloco_plan_kappa(const sparseloco_plan* plan);
+int sparseloco_plan_quant_mode(const sparseloco_plan* plan);
+/* SPLC_SELECT_*: which selection algorithm the compress kernel uses. */
+int sparseloco_plan_set_select(sparseloco_plan* plan, int select_mode);
+
+/*
+ * Lines 1-4 of the update equations for ONE replica, all tensors, one launch.
+ *   delta_mode = SPLC_DELTA_FROM_PARAMS: src_a = theta_outer[n_tensors],
+ *       src_b = theta_local[n_tensors], src_dtype must be SPLC_F32.
+ *   delta_mode = SPLC_DELTA_DIRECT: src_a = delta[n_tensors] of src_dtype,
+ *       src_b = NULL.
+ *   ef[n_tensors]: fp32 error-feedback buffers, read and rewritten in place.
+ *   beta: error-feedback momentum (0.95 in the paper).
+ *   pairs_out: uint16[n_chunks * kappa]; aux_out: float[n_chunks * 2] (2-bit
+ *   mode: scales) or float[n_chunks * kappa] (identity mode: values).  Both are
+ *   fully overwritten.  Sources are never written.  No buffer may overlap
+ *   another.
+ */
+int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype,
+                        const void* const* src_a, const void* const* src_b,
+                        float* const* ef, float beta,
+                        uint16_t* pairs_out, float* aux_out, void* stream);
+
+/*
+ * Line 5, first half: the mean over n_replicas (the paper's M) of the decoded
+ * messages.  pairs[r], aux[r]: replica r's message as written by
+ * sparseloco_compress with the same plan.  Per element the contributions are
+ * added in ascending replica order starting from +0, then divided once by
+ * (float)n_replicas; the result does not depend on scheduling (no float
+ * atomics).  delta_bar_out[n_tensors]: dense fp32, fully overwritten (zero
+ * where no replica sent anything).  1 <= n_replicas <= 1024.
+ */
+int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas,
+                         const uint16_t* const* pairs, const float* const* aux,
+                         float* const* delta_bar_out, void* stream);
+
+/*
+ * Line 5, second half: theta_outer[i] -= outer_lr * delta_bar[i], in place
+ * (outer SGD without momentum; outer_lr = 1.0 in the paper's runs).
+ */
+int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer,
+                            const float* const* delta_bar, float outer_lr, void* stream);
+
+const char* sparseloco_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

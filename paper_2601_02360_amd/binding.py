@@ -1,0 +1,177 @@
+"""Thin ctypes binding of libsparseloco.so: argument marshalling only.
+
+Every step of the outer step (paper section 2.1) runs in the library's HIP
+kernels; this module turns torch tensors into device pointers and passes the
+current HIP stream.  There is no fallback: if the library has not been built
+(`python -m paper_2601_02360_amd.build`) importing `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsparseloco.so")
+
+SPLC_CHUNK = 4096
+SPLC_OK, SPLC_EINVAL, SPLC_EALIGN, SPLC_ENOMEM, SPLC_EHIP, SPLC_EPLAN = 0, -1, -2, -3, -4, -5
+SPLC_F32, SPLC_BF16 = 0, 1
+SPLC_DELTA_FROM_PARAMS, SPLC_DELTA_DIRECT = 0, 1
+SPLC_QUANT_NONE, SPLC_QUANT_2BIT = 0, 1
+SPLC_SELECT_AUTO, SPLC_SELECT_RADIX = 0, 1
+
+EXPORTS = [
+    "sparseloco_plan_create", "sparseloco_plan_destroy", "sparseloco_plan_num_chunks",
+    "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
+    "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
+    "sparseloco_outer_update", "sparseloco_strerror",
+]
+
+_lib = None
+
+
+class SparseLoCoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().sparseloco_strerror(status).decode()
+        super().__init__("%s: %s (%d)" % (where, msg, status))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libsparseloco.so is not built; run `python -m paper_2601_02360_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        L.sparseloco_plan_create.restype = i32
+        L.sparseloco_plan_create.argtypes = [pp, i32, ctypes.POINTER(i64), i32, i32]
+        L.sparseloco_plan_destroy.restype = None
+        L.sparseloco_plan_destroy.argtypes = [vp]
+        L.sparseloco_plan_num_chunks.restype = i64
+        L.sparseloco_plan_num_chunks.argtypes = [vp]
+        L.sparseloco_plan_num_params.restype = i64
+        L.sparseloco_plan_num_params.argtypes = [vp]
+        L.sparseloco_plan_kappa.restype = i32
+        L.sparseloco_plan_kappa.argtypes = [vp]
+        L.sparseloco_plan_quant_mode.restype = i32
+        L.sparseloco_plan_quant_mode.argtypes = [vp]
+        L.sparseloco_plan_set_select.restype = i32
+        L.sparseloco_plan_set_select.argtypes = [vp, i32]
+        L.sparseloco_compress.restype = i32
+        L.sparseloco_compress.argtypes = [vp, i32, i32, pp, pp, pp, f32, vp, vp, vp]
+        L.sparseloco_aggregate.restype = i32
+        L.sparseloco_aggregate.argtypes = [vp, i32, pp, pp, pp, vp]
+        L.sparseloco_outer_update.restype = i32
+        L.sparseloco_outer_update.argtypes = [vp, pp, pp, f32, vp]
+        L.sparseloco_strerror.restype = ctypes.c_char_p
+        L.sparseloco_strerror.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def ptr_table(tensors: Sequence[Optional[torch.Tensor]]):
+    """Host array of device pointers for a list of tensors (build once, reuse across calls)."""
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = None if t is None or t.numel() == 0 else t.data_ptr()
+    return arr
+
+
+def _table(x):
+    return x if isinstance(x, ctypes.Array) else ptr_table(x)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    h = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return h or None
+
+
+class Plan:
+    """Chunk table and staging slots for a list of tensor sizes (sparseloco_plan_create)."""
+
+    def __init__(self, numels: Sequence[int], kappa: int, quant: bool = True):
+        self._h = ctypes.c_void_p()
+        n = len(numels)
+        arr = (ctypes.c_int64 * max(n, 1))(*[int(v) for v in numels])
+        rc = lib().sparseloco_plan_create(ctypes.byref(self._h), n, arr, int(kappa),
+                                          SPLC_QUANT_2BIT if quant else SPLC_QUANT_NONE)
+        if rc != SPLC_OK:
+            self._h = ctypes.c_void_p()
+            raise SparseLoCoError(rc, "sparseloco_plan_create")
+        self.numels = [int(v) for v in numels]
+        self.kappa = int(kappa)
+        self.quant = bool(quant)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().sparseloco_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def num_chunks(self) -> int:
+        return int(lib().sparseloco_plan_num_chunks(self._h))
+
+    @property
+    def num_params(self) -> int:
+        return int(lib().sparseloco_plan_num_params(self._h))
+
+    def set_select(self, mode: int) -> None:
+        rc = lib().sparseloco_plan_set_select(self._h, int(mode))
+        if rc != SPLC_OK:
+            raise SparseLoCoError(rc, "sparseloco_plan_set_select")
+
+    def message_buffers(self, device="cuda"):
+        """Freshly allocated (pairs, aux) for one replica's message."""
+        nch = self.num_chunks
+        pairs = torch.empty(nch * self.kappa, dtype=torch.int16, device=device)
+        aux = torch.empty(nch * 2 if self.quant else nch * self.kappa, dtype=torch.float32, device=device)
+        return pairs, aux
+
+
+def sparseloco_compress(plan: Plan, ef, pairs_out: torch.Tensor, aux_out: torch.Tensor, beta: float, *,
+                        theta_outer=None, theta_local=None, delta=None, delta_dtype=SPLC_F32, stream=None) -> None:
+    """Lines 1-4 of the update equations for one replica.  ef / theta_* / delta: lists of
+    tensors or prebuilt ptr_table()s."""
+    if delta is not None:
+        mode, a, b = SPLC_DELTA_DIRECT, _table(delta), None
+        if not isinstance(delta, ctypes.Array) and len(delta) and delta[0].dtype == torch.bfloat16:
+            delta_dtype = SPLC_BF16
+    else:
+        mode, a, b, delta_dtype = SPLC_DELTA_FROM_PARAMS, _table(theta_outer), _table(theta_local), SPLC_F32
+    rc = lib().sparseloco_compress(plan.handle, mode, delta_dtype, a, b, _table(ef), float(beta),
+                                   pairs_out.data_ptr(), aux_out.data_ptr(), _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_compress")
+
+
+def sparseloco_aggregate(plan: Plan, pairs, aux, delta_bar_out, *, stream=None) -> None:
+    """Mean over replicas of the decoded messages into dense fp32 tensors."""
+    pt, at = _table(pairs), _table(aux)
+    rc = lib().sparseloco_aggregate(plan.handle, len(pt), pt, at, _table(delta_bar_out), _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_aggregate")
+
+
+def sparseloco_outer_update(plan: Plan, theta_outer, delta_bar, outer_lr: float, *, stream=None) -> None:
+    """theta_outer -= outer_lr * delta_bar, in place."""
+    rc = lib().sparseloco_outer_update(plan.handle, _table(theta_outer), _table(delta_bar), float(outer_lr),
+                                       _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_outer_update")

@@ -1,0 +1,800 @@
+// SparseLoCo outer step for gfx950 (MI355X): kernels and C ABI.
+//
+// The three entry points follow the update equations of section 2.1 of the
+// paper (pseudo-gradient, error-feedback fold, chunk Top-kappa, Q, residual;
+// mean over replicas; outer SGD).  Nothing here is a dense contraction, so no
+// matrix cores are used: the kernels stream 16-byte-per-lane loads, keep each
+// 4096-element chunk in registers (16 values per lane, 256 lanes) and use LDS
+// only for the small hand-offs of the selection.
+//
+// Element layout of a chunk inside a workgroup: lane `tid` holds, for slot
+// s = 0..3 and j = 0..3, element index  s*1024 + tid*4 + j  (one float4 per
+// slot), so every load instruction of the workgroup covers 4 KiB contiguous.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "sparseloco.h"
+
+namespace {
+
+constexpr int kChunk = SPLC_CHUNK;
+constexpr int kThreads = 256;            // one workgroup per chunk
+constexpr int kCandCap = 256;            // candidates the exact ranking handles (one per lane)
+constexpr int kFilterKappaMax = 256;     // the candidate filter needs kappa <= number of lanes
+constexpr int kSlots = 32;               // staging slots for pointer tables
+constexpr int kMaxReplicas = 1024;
+
+struct ChunkDesc {
+    uint32_t tensor;                     // index into the pointer tables
+    uint32_t n_c;                        // elements in this chunk (kChunk except a tensor's last)
+    uint64_t offset;                     // element offset of the chunk inside its tensor
+};
+
+enum { MODE_PARAMS_F32 = 0, MODE_DIRECT_F32 = 1, MODE_DIRECT_BF16 = 2 };
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        uint32_t other = (uint32_t)__shfl_xor((int)v, o);
+        v = other > v ? other : v;
+    }
+    return v;
+}
+
+// e' = fl(fl(beta * e) + delta), delta = fl(theta_outer - theta_local) or given (section 2.1, lines 1-2).
+__device__ __forceinline__ float fold(float beta, float e, float delta) {
+    return __fadd_rn(__fmul_rn(beta, e), delta);
+}
+
+template <int MODE>
+__device__ __forceinline__ void load_fold_full(const void* __restrict__ a, const void* __restrict__ b,
+                                               const float* __restrict__ e, uint64_t off, int tid, float beta,
+                                               float (&x)[16]) {
+    const float4* pe = reinterpret_cast<const float4*>(e + off);
+    float4 ev[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) ev[s] = pe[s * kThreads + tid];
+    if (MODE == MODE_PARAMS_F32) {
+        const float4* po = reinterpret_cast<const float4*>(static_cast<const float*>(a) + off);
+        const float4* pl = reinterpret_cast<const float4*>(static_cast<const float*>(b) + off);
+        float4 ov[4], lv[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) ov[s] = po[s * kThreads + tid];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) lv[s] = pl[s * kThreads + tid];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            x[4 * s + 0] = fold(beta, ev[s].x, __fsub_rn(ov[s].x, lv[s].x));
+            x[4 * s + 1] = fold(beta, ev[s].y, __fsub_rn(ov[s].y, lv[s].y));
+            x[4 * s + 2] = fold(beta, ev[s].z, __fsub_rn(ov[s].z, lv[s].z));
+            x[4 * s + 3] = fold(beta, ev[s].w, __fsub_rn(ov[s].w, lv[s].w));
+        }
+    } else if (MODE == MODE_DIRECT_F32) {
+        const float4* pd = reinterpret_cast<const float4*>(static_cast<const float*>(a) + off);
+        float4 dv[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) dv[s] = pd[s * kThreads + tid];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            x[4 * s + 0] = fold(beta, ev[s].x, dv[s].x);
+            x[4 * s + 1] = fold(beta, ev[s].y, dv[s].y);
+            x[4 * s + 2] = fold(beta, ev[s].z, dv[s].z);
+            x[4 * s + 3] = fold(beta, ev[s].w, dv[s].w);
+        }
+    } else {
+        // bf16 -> fp32 is the exact widening: the 16 bits become the upper half of the word
+        const uint2* pd = reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a) + off);
+        uint2 dv[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) dv[s] = pd[s * kThreads + tid];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            x[4 * s + 0] = fold(beta, ev[s].x, __uint_as_float(dv[s].x << 16));
+            x[4 * s + 1] = fold(beta, ev[s].y, __uint_as_float(dv[s].x & 0xFFFF0000u));
+            x[4 * s + 2] = fold(beta, ev[s].z, __uint_as_float(dv[s].y << 16));
+            x[4 * s + 3] = fold(beta, ev[s].w, __uint_as_float(dv[s].y & 0xFFFF0000u));
+        }
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void load_fold_partial(const void* __restrict__ a, const void* __restrict__ b,
+                                                  const float* __restrict__ e, uint64_t off, int tid, float beta,
+                                                  uint32_t n_c, float (&x)[16]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t idx = s * 1024 + tid * 4 + j;
+            float v = 0.f;
+            if (idx < n_c) {
+                float ev = e[off + idx];
+                float d;
+                if (MODE == MODE_PARAMS_F32)
+                    d = __fsub_rn(static_cast<const float*>(a)[off + idx], static_cast<const float*>(b)[off + idx]);
+                else if (MODE == MODE_DIRECT_F32)
+                    d = static_cast<const float*>(a)[off + idx];
+                else
+                    d = __uint_as_float((uint32_t) static_cast<const uint16_t*>(a)[off + idx] << 16);
+                v = fold(beta, ev, d);
+            }
+            x[4 * s + j] = v;
+        }
+    }
+}
+
+// Shared state of one chunk's selection.
+struct SelectShared {
+    uint64_t cand[kCandCap + 2];         // (key << 12 | 4095 - idx) of the candidates, zero padded
+    uint32_t hist[256];                  // radix select digit histogram
+    uint32_t bucket[16];                 // selected entries per 256-element bucket (bucket = idx >> 8)
+    uint32_t t0[4];                      // per-wave lower bounds of the threshold
+    uint32_t wmax[4];                    // per-wave maxima of the keys (largest selected magnitude)
+    uint64_t thr;                        // composite of the kappa_c-th entry in (key desc, idx asc) order
+    uint32_t ncand;
+    uint32_t digit;
+    uint32_t need;
+};
+
+// Exact kappa_c-th largest composite by most-significant-digit radix select over
+// the 43-bit composites (31 key bits, 12 inverted index bits).  Composites of
+// valid elements are distinct, so the result identifies one element: the last
+// one kept.  Works for any n_c <= 4096, any kappa_c in 1..n_c, any tie pattern.
+__device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, uint32_t n_c, uint32_t kappa_c) {
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    uint64_t prefix = 0;
+    uint32_t need = kappa_c;
+    int hi_bit = 43;
+#pragma unroll 1
+    for (int pass = 0; pass < 6; ++pass) {
+        const int width = pass < 5 ? 8 : 3;
+        const int shift = hi_bit - width;
+        sh.hist[tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int el = 0; el < 16; ++el) {
+            uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+            uint64_t comp = ((uint64_t)(__float_as_uint(x[el]) & 0x7FFFFFFFu) << 12) | (uint64_t)(4095u - idx);
+            if (idx < n_c && (comp >> hi_bit) == prefix)
+                atomicAdd(&sh.hist[(uint32_t)(comp >> shift) & ((1u << width) - 1u)], 1u);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane owns bins 4*lane .. 4*lane+3; find the bin where the count from the top reaches `need`
+            uint32_t h0 = sh.hist[4 * lane], h1 = sh.hist[4 * lane + 1], h2 = sh.hist[4 * lane + 2],
+                     h3 = sh.hist[4 * lane + 3];
+            uint32_t own = h0 + h1 + h2 + h3;
+            uint32_t suffix = own;               // inclusive sum over lanes >= this one
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                uint32_t v = (uint32_t)__shfl_down((int)suffix, o);
+                if (lane + o < 64) suffix += v;
+            }
+            uint32_t above = suffix - own;
+            if (above < need && need <= suffix) {
+                uint32_t bin;
+                if (above + h3 >= need) bin = 3;
+                else { above += h3;
+                    if (above + h2 >= need) bin = 2;
+                    else { above += h2;
+                        if (above + h1 >= need) bin = 1;
+                        else { above += h1; bin = 0; } } }
+                sh.digit = 4 * lane + bin;
+                sh.need = need - above;
+            }
+        }
+        __syncthreads();
+        prefix = (prefix << width) | (uint64_t)sh.digit;
+        need = sh.need;
+        hi_bit = shift;
+    }
+    // publish the threshold, the largest key and the selected count of every 256-element bucket
+    uint32_t tmax = 0;
+#pragma unroll
+    for (int el = 0; el < 16; ++el) {
+        uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+        uint32_t key = __float_as_uint(x[el]) & 0x7FFFFFFFu;
+        uint64_t comp = ((uint64_t)key << 12) | (uint64_t)(4095u - idx);
+        if (idx < n_c) {
+            tmax = key > tmax ? key : tmax;
+            if (comp >= prefix) atomicAdd(&sh.bucket[idx >> 8], 1u);
+        }
+    }
+    tmax = wave_max_u32(tmax);
+    if (lane == 0) sh.wmax[wave] = tmax;
+    if (tid == 0) sh.thr = prefix;
+    __syncthreads();
+}
+
+// Lines 1-4 of the update equations for one chunk per workgroup.
+template <int MODE, int QUANT>
+__global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __restrict__ chunks,
+                                                            const void* const* __restrict__ src_a,
+                                                            const void* const* __restrict__ src_b,
+                                                            float* const* __restrict__ ef_tab, float beta,
+                                                            uint32_t kappa, int force_radix,
+                                                            uint16_t* __restrict__ pairs_out,
+                                                            float* __restrict__ aux_out) {
+    __shared__ __align__(16) SelectShared sh;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint64_t c = blockIdx.x;
+    const ChunkDesc d = chunks[c];
+    const uint32_t n_c = d.n_c;
+    const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
+    const void* pa = src_a[d.tensor];
+    const void* pb = MODE == MODE_PARAMS_F32 ? src_b[d.tensor] : nullptr;
+    float* pe = ef_tab[d.tensor];
+
+    float x[16];
+    if (n_c == (uint32_t)kChunk) load_fold_full<MODE>(pa, pb, pe, d.offset, tid, beta, x);
+    else load_fold_partial<MODE>(pa, pb, pe, d.offset, tid, beta, n_c, x);
+
+    sh.cand[tid] = 0;
+    if (tid < 2) sh.cand[kCandCap + tid] = 0;
+    if (tid < 16) sh.bucket[tid] = 0;
+    if (tid < 4) sh.wmax[tid] = 0;
+    if (tid == 0) sh.ncand = 0;
+
+    bool selected_by_filter = false;
+    if (n_c == (uint32_t)kChunk && kappa <= (uint32_t)kFilterKappaMax && !force_radix) {
+        // ---- candidate filter: a lower bound T0 of the threshold from the lane maxima ----
+        uint32_t key[16];
+#pragma unroll
+        for (int el = 0; el < 16; ++el) key[el] = __float_as_uint(x[el]) & 0x7FFFFFFFu;
+        uint32_t tmax = key[0];
+#pragma unroll
+        for (int el = 1; el < 16; ++el) tmax = key[el] > tmax ? key[el] : tmax;
+        // Largest X (low 10 bits zero) with at least m lane maxima >= X in this wave.  Each of those
+        // lanes holds a distinct element >= X, so over four waves at least 4*m >= kappa elements are
+        // >= min X: the threshold cannot be below it.
+        const uint32_t m = (kappa + 3) >> 2;
+        uint32_t X = 0;
+#pragma unroll
+        for (int b = 30; b >= 10; --b) {
+            uint32_t t = X | (1u << b);
+            uint32_t cnt = (uint32_t)__popcll(__ballot(tmax >= t));
+            X = cnt >= m ? t : X;
+        }
+        if (lane == 0) sh.t0[wave] = X;
+        __syncthreads();
+        uint32_t T0 = sh.t0[0];
+        T0 = sh.t0[1] < T0 ? sh.t0[1] : T0;
+        T0 = sh.t0[2] < T0 ? sh.t0[2] : T0;
+        T0 = sh.t0[3] < T0 ? sh.t0[3] : T0;
+
+        // ---- compact the candidates (key >= T0) into LDS, wave by wave ----
+        uint64_t msk[16];
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int el = 0; el < 16; ++el) {
+            msk[el] = __ballot(key[el] >= T0);
+            cnt += (uint32_t)__popcll(msk[el]);
+        }
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&sh.ncand, cnt);
+        base = __builtin_amdgcn_readfirstlane(base);
+        if (base + cnt <= (uint32_t)kCandCap) {
+            uint32_t run = base;
+#pragma unroll
+            for (int el = 0; el < 16; ++el) {
+                if (msk[el] != 0) {
+                    if (key[el] >= T0) {
+                        uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+                        sh.cand[run + lanes_below(msk[el])] = ((uint64_t)key[el] << 12) | (uint64_t)(4095u - idx);
+                    }
+                    run += (uint32_t)__popcll(msk[el]);
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t n = sh.ncand;
+        if (n <= (uint32_t)kCandCap) {
+            // ---- exact rank of every candidate among the candidates (composites are distinct) ----
+            if ((uint32_t)tid < n) {
+                const uint64_t mine = sh.cand[tid];
+                uint32_t rank = 0;
+                for (uint32_t i = 0; i < n; i += 2) {
+                    uint64_t c0 = sh.cand[i], c1 = sh.cand[i + 1];
+                    rank += (c0 > mine ? 1u : 0u) + (c1 > mine ? 1u : 0u);
+                }
+                if (rank == kappa - 1) sh.thr = mine;
+                if (rank == 0) sh.wmax[0] = (uint32_t)(mine >> 12);
+                if (rank < kappa) atomicAdd(&sh.bucket[(4095u - ((uint32_t)mine & 4095u)) >> 8], 1u);
+            }
+            selected_by_filter = true;
+        }
+    }
+    __syncthreads();
+    if (!selected_by_filter) radix_select(sh, x, tid, n_c, kappa_c);
+
+    // ---- final pass: selection predicate, output positions, quantise, pack, residual ----
+    const uint64_t thr = sh.thr;
+    const uint32_t T = (uint32_t)(thr >> 12);
+    const uint32_t idxT = 4095u - ((uint32_t)thr & 4095u);
+    uint32_t amax_k = sh.wmax[0];
+    amax_k = sh.wmax[1] > amax_k ? sh.wmax[1] : amax_k;
+    amax_k = sh.wmax[2] > amax_k ? sh.wmax[2] : amax_k;
+    amax_k = sh.wmax[3] > amax_k ? sh.wmax[3] : amax_k;
+    // The smallest selected magnitude is the threshold key itself; the largest is the chunk maximum.
+    const float amin = __uint_as_float(T), amax = __uint_as_float(amax_k);
+    const float dd = __fsub_rn(amax, amin);
+    const float lo = __fadd_rn(amin, __fmul_rn(0.25f, dd));
+    const float tau = __fadd_rn(amin, __fmul_rn(0.5f, dd));
+    const float hi = __fadd_rn(amin, __fmul_rn(0.75f, dd));
+    const uint32_t tau_bits = __float_as_uint(tau);
+
+    uint32_t base_of_slot[4];
+    {
+        uint32_t run = 0;
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+            if ((b & 3) == wave) base_of_slot[b >> 2] = run;
+            run += sh.bucket[b];
+        }
+    }
+    uint16_t* pairs_c = pairs_out + c * kappa;
+    float* values_c = aux_out + c * kappa;          // identity mode only
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        bool sel[4];
+        uint64_t m4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t idx = s * 1024 + tid * 4 + j;
+            uint32_t key = __float_as_uint(x[4 * s + j]) & 0x7FFFFFFFu;
+            sel[j] = idx < n_c && (key > T || (key == T && idx <= idxT));
+            m4[j] = __ballot(sel[j]);
+        }
+        if ((m4[0] | m4[1] | m4[2] | m4[3]) != 0) {
+            uint32_t pos = base_of_slot[s] + lanes_below(m4[0]) + lanes_below(m4[1]) + lanes_below(m4[2]) +
+                           lanes_below(m4[3]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (sel[j]) {
+                    uint32_t idx = s * 1024 + tid * 4 + j;
+                    uint32_t bits = __float_as_uint(x[4 * s + j]);
+                    if (QUANT == SPLC_QUANT_2BIT) {
+                        uint32_t upper = (bits & 0x7FFFFFFFu) >= tau_bits ? 1u : 0u;
+                        uint32_t sign = bits >> 31;
+                        float q = __uint_as_float(__float_as_uint(upper ? hi : lo) | (bits & 0x80000000u));
+                        pairs_c[pos] = (uint16_t)(idx | (((sign << 1) | upper) << 12));
+                        x[4 * s + j] = __fsub_rn(x[4 * s + j], q);
+                    } else {
+                        pairs_c[pos] = (uint16_t)idx;
+                        values_c[pos] = x[4 * s + j];
+                        x[4 * s + j] = __fsub_rn(x[4 * s + j], x[4 * s + j]);
+                    }
+                    ++pos;
+                }
+            }
+        }
+    }
+    for (uint32_t t = kappa_c + tid; t < kappa; t += kThreads) {
+        pairs_c[t] = 0xFFFFu;
+        if (QUANT == SPLC_QUANT_NONE) values_c[t] = 0.f;
+    }
+    if (QUANT == SPLC_QUANT_2BIT && tid == 0) {
+        aux_out[2 * c] = lo;
+        aux_out[2 * c + 1] = hi;
+    }
+
+    // ---- the error-feedback buffer is rewritten densely ----
+    if (n_c == (uint32_t)kChunk) {
+        float4* po = reinterpret_cast<float4*>(pe + d.offset);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            po[s * kThreads + tid] = make_float4(x[4 * s], x[4 * s + 1], x[4 * s + 2], x[4 * s + 3]);
+    } else {
+#pragma unroll
+        for (int el = 0; el < 16; ++el) {
+            uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+            if (idx < n_c) pe[d.offset + idx] = x[el];
+        }
+    }
+}
+
+// Line 5, first half: mean over replicas.  One workgroup per chunk; a dense fp32
+// accumulator of the chunk lives in LDS.  Replicas are applied one after the
+// other with a barrier in between; inside one replica the indices are distinct,
+// so every element sees its addends in ascending replica order.
+template <int QUANT>
+__global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __restrict__ chunks, int n_replicas,
+                                                             uint32_t kappa,
+                                                             const uint16_t* const* __restrict__ pairs_tab,
+                                                             const float* const* __restrict__ aux_tab,
+                                                             float* const* __restrict__ out_tab) {
+    __shared__ __align__(16) float acc[kChunk];
+    const int tid = threadIdx.x;
+    const uint64_t c = blockIdx.x;
+    const ChunkDesc d = chunks[c];
+    const uint32_t n_c = d.n_c;
+    const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
+    float4* acc4 = reinterpret_cast<float4*>(acc);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) acc4[s * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+    for (int r = 0; r < n_replicas; ++r) {
+        const uint16_t* pr = pairs_tab[r] + c * kappa;
+        const float* ar = aux_tab[r];
+        float lo = 0.f, hi = 0.f;
+        if (QUANT == SPLC_QUANT_2BIT) { lo = ar[2 * c]; hi = ar[2 * c + 1]; }
+        for (uint32_t t = tid; t < kappa_c; t += kThreads) {
+            uint32_t p = pr[t];
+            uint32_t idx = p & 0xFFFu;
+            float q;
+            if (QUANT == SPLC_QUANT_2BIT) {
+                float level = (p & 0x1000u) ? hi : lo;
+                q = (p & 0x2000u) ? -level : level;
+            } else {
+                q = ar[c * kappa + t];
+            }
+            if (idx < n_c) acc[idx] = __fadd_rn(acc[idx], q);
+        }
+        __syncthreads();
+    }
+    const float m = (float)n_replicas;
+    float* po = out_tab[d.tensor] + d.offset;
+    if (n_c == (uint32_t)kChunk) {
+        float4* po4 = reinterpret_cast<float4*>(po);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float4 v = acc4[s * kThreads + tid];
+            v.x = __fdiv_rn(v.x, m); v.y = __fdiv_rn(v.y, m); v.z = __fdiv_rn(v.z, m); v.w = __fdiv_rn(v.w, m);
+            po4[s * kThreads + tid] = v;
+        }
+    } else {
+        for (uint32_t idx = tid; idx < n_c; idx += kThreads) po[idx] = __fdiv_rn(acc[idx], m);
+    }
+}
+
+// Line 5, second half: theta = fl(theta - fl(eta * delta_bar)).
+__global__ __launch_bounds__(kThreads) void outer_update_kernel(const ChunkDesc* __restrict__ chunks,
+                                                                float* const* __restrict__ theta_tab,
+                                                                const float* const* __restrict__ dbar_tab,
+                                                                float eta) {
+    const int tid = threadIdx.x;
+    const ChunkDesc d = chunks[blockIdx.x];
+    float* th = theta_tab[d.tensor] + d.offset;
+    const float* db = dbar_tab[d.tensor] + d.offset;
+    if (d.n_c == (uint32_t)kChunk) {
+        float4* th4 = reinterpret_cast<float4*>(th);
+        const float4* db4 = reinterpret_cast<const float4*>(db);
+        float4 t[4], g[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) t[s] = th4[s * kThreads + tid];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) g[s] = db4[s * kThreads + tid];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            t[s].x = __fsub_rn(t[s].x, __fmul_rn(eta, g[s].x));
+            t[s].y = __fsub_rn(t[s].y, __fmul_rn(eta, g[s].y));
+            t[s].z = __fsub_rn(t[s].z, __fmul_rn(eta, g[s].z));
+            t[s].w = __fsub_rn(t[s].w, __fmul_rn(eta, g[s].w));
+            th4[s * kThreads + tid] = t[s];
+        }
+    } else {
+        for (uint32_t idx = tid; idx < d.n_c; idx += kThreads)
+            th[idx] = __fsub_rn(th[idx], __fmul_rn(eta, db[idx]));
+    }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ host side
+
+struct sparseloco_plan {
+    int device = 0;
+    int n_tensors = 0;
+    int kappa = 0;
+    int quant = SPLC_QUANT_2BIT;
+    int select = SPLC_SELECT_AUTO;
+    int64_t n_chunks = 0;
+    int64_t n_params = 0;
+    std::vector<int64_t> numel;
+    ChunkDesc* d_chunks = nullptr;
+    // ring of staging slots for the per-call pointer tables
+    size_t slot_bytes = 0;
+    char* h_slots = nullptr;             // pinned host memory, kSlots * slot_bytes
+    char* d_slots = nullptr;             // device memory, kSlots * slot_bytes
+    hipEvent_t ev[kSlots] = {};
+    bool ev_used[kSlots] = {};
+    int next_slot = 0;
+};
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Reserve the next staging slot (waiting for the work that last used it) and return its host buffer.
+int slot_acquire(sparseloco_plan* plan, int* slot, char** host) {
+    int s = plan->next_slot;
+    if (plan->ev_used[s] && hipEventSynchronize(plan->ev[s]) != hipSuccess) return SPLC_EHIP;
+    plan->next_slot = (s + 1) % kSlots;
+    *slot = s;
+    *host = plan->h_slots + (size_t)s * plan->slot_bytes;
+    return SPLC_OK;
+}
+
+int slot_upload(sparseloco_plan* plan, int slot, size_t bytes, hipStream_t stream, char** dev) {
+    char* h = plan->h_slots + (size_t)slot * plan->slot_bytes;
+    char* dptr = plan->d_slots + (size_t)slot * plan->slot_bytes;
+    if (hipMemcpyAsync(dptr, h, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return SPLC_EHIP;
+    *dev = dptr;
+    return SPLC_OK;
+}
+
+int slot_release(sparseloco_plan* plan, int slot, hipStream_t stream) {
+    if (hipEventRecord(plan->ev[slot], stream) != hipSuccess) return SPLC_EHIP;
+    plan->ev_used[slot] = true;
+    return SPLC_OK;
+}
+
+int check_device(const sparseloco_plan* plan) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SPLC_EHIP;
+    return dev == plan->device ? SPLC_OK : SPLC_EPLAN;
+}
+
+template <int MODE, int QUANT>
+void launch_compress(const sparseloco_plan* plan, const void* const* a, const void* const* b, float* const* ef,
+                     float beta, uint16_t* pairs_out, float* aux_out, hipStream_t stream) {
+    hipLaunchKernelGGL((compress_kernel<MODE, QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
+                       plan->d_chunks, a, b, ef, beta, (uint32_t)plan->kappa,
+                       plan->select == SPLC_SELECT_RADIX ? 1 : 0, pairs_out, aux_out);
+}
+
+}  // namespace
+
+extern "C" {
+
+int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel, int kappa, int quant_mode) {
+    if (!out) return SPLC_EINVAL;
+    *out = nullptr;
+    if (n_tensors < 1 || !numel || kappa < 1 || kappa > kChunk) return SPLC_EINVAL;
+    if (quant_mode != SPLC_QUANT_NONE && quant_mode != SPLC_QUANT_2BIT) return SPLC_EINVAL;
+    int64_t n_chunks = 0, n_params = 0;
+    for (int i = 0; i < n_tensors; ++i) {
+        if (numel[i] < 0) return SPLC_EINVAL;
+        n_chunks += (numel[i] + kChunk - 1) / kChunk;
+        n_params += numel[i];
+    }
+    if (n_chunks > 0x7FFFFFFF) return SPLC_EINVAL;      // one workgroup per chunk in a 1-D grid
+    sparseloco_plan* plan = new (std::nothrow) sparseloco_plan();
+    if (!plan) return SPLC_ENOMEM;
+    if (hipGetDevice(&plan->device) != hipSuccess) { delete plan; return SPLC_EHIP; }
+    plan->n_tensors = n_tensors;
+    plan->kappa = kappa;
+    plan->quant = quant_mode;
+    plan->n_chunks = n_chunks;
+    plan->n_params = n_params;
+    plan->numel.assign(numel, numel + n_tensors);
+
+    std::vector<ChunkDesc> table;
+    table.reserve((size_t)n_chunks);
+    for (int i = 0; i < n_tensors; ++i) {
+        for (int64_t off = 0; off < numel[i]; off += kChunk) {
+            ChunkDesc cd;
+            cd.tensor = (uint32_t)i;
+            cd.n_c = (uint32_t)((numel[i] - off) < kChunk ? (numel[i] - off) : kChunk);
+            cd.offset = (uint64_t)off;
+            table.push_back(cd);
+        }
+    }
+    int rc = SPLC_OK;
+    size_t n_ptrs = (size_t)3 * (size_t)n_tensors;
+    if (n_ptrs < (size_t)n_tensors + 2 * (size_t)kMaxReplicas) n_ptrs = (size_t)n_tensors + 2 * (size_t)kMaxReplicas;
+    plan->slot_bytes = (n_ptrs * sizeof(void*) + 255) & ~(size_t)255;
+    if (n_chunks > 0 &&
+        hipMalloc(reinterpret_cast<void**>(&plan->d_chunks), (size_t)n_chunks * sizeof(ChunkDesc)) != hipSuccess)
+        rc = SPLC_ENOMEM;
+    if (rc == SPLC_OK && n_chunks > 0 &&
+        hipMemcpy(plan->d_chunks, table.data(), (size_t)n_chunks * sizeof(ChunkDesc), hipMemcpyHostToDevice) !=
+            hipSuccess)
+        rc = SPLC_EHIP;
+    if (rc == SPLC_OK &&
+        hipHostMalloc(reinterpret_cast<void**>(&plan->h_slots), kSlots * plan->slot_bytes, hipHostMallocDefault) !=
+            hipSuccess)
+        rc = SPLC_ENOMEM;
+    if (rc == SPLC_OK &&
+        hipMalloc(reinterpret_cast<void**>(&plan->d_slots), kSlots * plan->slot_bytes) != hipSuccess)
+        rc = SPLC_ENOMEM;
+    for (int s = 0; rc == SPLC_OK && s < kSlots; ++s)
+        if (hipEventCreateWithFlags(&plan->ev[s], hipEventDisableTiming) != hipSuccess) rc = SPLC_EHIP;
+    if (rc != SPLC_OK) {
+        sparseloco_plan_destroy(plan);
+        return rc;
+    }
+    *out = plan;
+    return SPLC_OK;
+}
+
+void sparseloco_plan_destroy(sparseloco_plan* plan) {
+    if (!plan) return;
+    for (int s = 0; s < kSlots; ++s) {
+        if (plan->ev[s]) {
+            if (plan->ev_used[s]) (void)hipEventSynchronize(plan->ev[s]);
+            (void)hipEventDestroy(plan->ev[s]);
+        }
+    }
+    if (plan->d_chunks) (void)hipFree(plan->d_chunks);
+    if (plan->d_slots) (void)hipFree(plan->d_slots);
+    if (plan->h_slots) (void)hipHostFree(plan->h_slots);
+    delete plan;
+}
+
+int64_t sparseloco_plan_num_chunks(const sparseloco_plan* plan) { return plan ? plan->n_chunks : SPLC_EINVAL; }
+int64_t sparseloco_plan_num_params(const sparseloco_plan* plan) { return plan ? plan->n_params : SPLC_EINVAL; }
+int sparseloco_plan_kappa(const sparseloco_plan* plan) { return plan ? plan->kappa : SPLC_EINVAL; }
+int sparseloco_plan_quant_mode(const sparseloco_plan* plan) { return plan ? plan->quant : SPLC_EINVAL; }
+
+int sparseloco_plan_set_select(sparseloco_plan* plan, int select_mode) {
+    if (!plan || (select_mode != SPLC_SELECT_AUTO && select_mode != SPLC_SELECT_RADIX)) return SPLC_EINVAL;
+    plan->select = select_mode;
+    return SPLC_OK;
+}
+
+int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype, const void* const* src_a,
+                        const void* const* src_b, float* const* ef, float beta, uint16_t* pairs_out,
+                        float* aux_out, void* stream) {
+    if (!plan || !src_a || !ef || !pairs_out || !aux_out) return SPLC_EINVAL;
+    int mode;
+    if (delta_mode == SPLC_DELTA_FROM_PARAMS) {
+        if (src_dtype != SPLC_F32 || !src_b) return SPLC_EINVAL;
+        mode = MODE_PARAMS_F32;
+    } else if (delta_mode == SPLC_DELTA_DIRECT) {
+        if (src_b) return SPLC_EINVAL;
+        if (src_dtype == SPLC_F32) mode = MODE_DIRECT_F32;
+        else if (src_dtype == SPLC_BF16) mode = MODE_DIRECT_BF16;
+        else return SPLC_EINVAL;
+    } else {
+        return SPLC_EINVAL;
+    }
+    if (!(beta == beta) || beta - beta != 0.f) return SPLC_EINVAL;      // finite
+    const size_t src_align = mode == MODE_DIRECT_BF16 ? 8 : 16;
+    for (int i = 0; i < plan->n_tensors; ++i) {
+        if (plan->numel[i] == 0) continue;
+        if (!src_a[i] || !ef[i] || (mode == MODE_PARAMS_F32 && !src_b[i])) return SPLC_EINVAL;
+        if (!aligned(src_a[i], src_align) || !aligned(ef[i], 16) ||
+            (mode == MODE_PARAMS_F32 && !aligned(src_b[i], 16)))
+            return SPLC_EALIGN;
+    }
+    if (!aligned(pairs_out, 2) || !aligned(aux_out, 4)) return SPLC_EALIGN;
+    int rc = check_device(plan);
+    if (rc != SPLC_OK) return rc;
+    if (plan->n_chunks == 0) return SPLC_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int slot;
+    char* h;
+    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
+    const size_t nt = (size_t)plan->n_tensors;
+    void** tab = reinterpret_cast<void**>(h);
+    for (size_t i = 0; i < nt; ++i) {
+        tab[i] = const_cast<void*>(src_a[i]);
+        tab[nt + i] = src_b ? const_cast<void*>(src_b[i]) : nullptr;
+        tab[2 * nt + i] = ef[i];
+    }
+    char* dtab;
+    if ((rc = slot_upload(plan, slot, 3 * nt * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
+    const void* const* da = reinterpret_cast<const void* const*>(dtab);
+    const void* const* db = reinterpret_cast<const void* const*>(dtab + nt * sizeof(void*));
+    float* const* de = reinterpret_cast<float* const*>(dtab + 2 * nt * sizeof(void*));
+    const bool q2 = plan->quant == SPLC_QUANT_2BIT;
+    switch (mode) {
+        case MODE_PARAMS_F32:
+            if (q2) launch_compress<MODE_PARAMS_F32, SPLC_QUANT_2BIT>(plan, da, db, de, beta, pairs_out, aux_out, st);
+            else launch_compress<MODE_PARAMS_F32, SPLC_QUANT_NONE>(plan, da, db, de, beta, pairs_out, aux_out, st);
+            break;
+        case MODE_DIRECT_F32:
+            if (q2) launch_compress<MODE_DIRECT_F32, SPLC_QUANT_2BIT>(plan, da, db, de, beta, pairs_out, aux_out, st);
+            else launch_compress<MODE_DIRECT_F32, SPLC_QUANT_NONE>(plan, da, db, de, beta, pairs_out, aux_out, st);
+            break;
+        default:
+            if (q2) launch_compress<MODE_DIRECT_BF16, SPLC_QUANT_2BIT>(plan, da, db, de, beta, pairs_out, aux_out, st);
+            else launch_compress<MODE_DIRECT_BF16, SPLC_QUANT_NONE>(plan, da, db, de, beta, pairs_out, aux_out, st);
+            break;
+    }
+    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
+    return slot_release(plan, slot, st);
+}
+
+int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
+                         const float* const* aux, float* const* delta_bar_out, void* stream) {
+    if (!plan || !pairs || !aux || !delta_bar_out) return SPLC_EINVAL;
+    if (n_replicas < 1 || n_replicas > kMaxReplicas) return SPLC_EINVAL;
+    for (int r = 0; r < n_replicas; ++r) {
+        if (!pairs[r] || !aux[r]) return SPLC_EINVAL;
+        if (!aligned(pairs[r], 2) || !aligned(aux[r], 4)) return SPLC_EALIGN;
+    }
+    for (int i = 0; i < plan->n_tensors; ++i) {
+        if (plan->numel[i] == 0) continue;
+        if (!delta_bar_out[i]) return SPLC_EINVAL;
+        if (!aligned(delta_bar_out[i], 16)) return SPLC_EALIGN;
+    }
+    int rc = check_device(plan);
+    if (rc != SPLC_OK) return rc;
+    if (plan->n_chunks == 0) return SPLC_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int slot;
+    char* h;
+    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
+    const size_t nt = (size_t)plan->n_tensors, nr = (size_t)n_replicas;
+    void** tab = reinterpret_cast<void**>(h);
+    for (size_t r = 0; r < nr; ++r) {
+        tab[r] = const_cast<uint16_t*>(pairs[r]);
+        tab[nr + r] = const_cast<float*>(aux[r]);
+    }
+    for (size_t i = 0; i < nt; ++i) tab[2 * nr + i] = delta_bar_out[i];
+    char* dtab;
+    if ((rc = slot_upload(plan, slot, (2 * nr + nt) * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
+    const uint16_t* const* dp = reinterpret_cast<const uint16_t* const*>(dtab);
+    const float* const* dx = reinterpret_cast<const float* const*>(dtab + nr * sizeof(void*));
+    float* const* dout = reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*));
+    if (plan->quant == SPLC_QUANT_2BIT)
+        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_2BIT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0,
+                           st, plan->d_chunks, n_replicas, (uint32_t)plan->kappa, dp, dx, dout);
+    else
+        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_NONE>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0,
+                           st, plan->d_chunks, n_replicas, (uint32_t)plan->kappa, dp, dx, dout);
+    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
+    return slot_release(plan, slot, st);
+}
+
+int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer, const float* const* delta_bar,
+                            float outer_lr, void* stream) {
+    if (!plan || !theta_outer || !delta_bar) return SPLC_EINVAL;
+    if (!(outer_lr == outer_lr) || outer_lr - outer_lr != 0.f) return SPLC_EINVAL;
+    for (int i = 0; i < plan->n_tensors; ++i) {
+        if (plan->numel[i] == 0) continue;
+        if (!theta_outer[i] || !delta_bar[i]) return SPLC_EINVAL;
+        if (!aligned(theta_outer[i], 16) || !aligned(delta_bar[i], 16)) return SPLC_EALIGN;
+    }
+    int rc = check_device(plan);
+    if (rc != SPLC_OK) return rc;
+    if (plan->n_chunks == 0) return SPLC_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int slot;
+    char* h;
+    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
+    const size_t nt = (size_t)plan->n_tensors;
+    void** tab = reinterpret_cast<void**>(h);
+    for (size_t i = 0; i < nt; ++i) {
+        tab[i] = theta_outer[i];
+        tab[nt + i] = const_cast<float*>(delta_bar[i]);
+    }
+    char* dtab;
+    if ((rc = slot_upload(plan, slot, 2 * nt * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
+    float* const* dth = reinterpret_cast<float* const*>(dtab);
+    const float* const* ddb = reinterpret_cast<const float* const*>(dtab + nt * sizeof(void*));
+    hipLaunchKernelGGL(outer_update_kernel, dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, st, plan->d_chunks,
+                       dth, ddb, outer_lr);
+    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
+    return slot_release(plan, slot, st);
+}
+
+const char* sparseloco_strerror(int status) {
+    switch (status) {
+        case SPLC_OK: return "ok";
+        case SPLC_EINVAL: return "invalid argument";
+        case SPLC_EALIGN: return "tensor pointer not sufficiently aligned";
+        case SPLC_ENOMEM: return "allocation failed";
+        case SPLC_EHIP: return "HIP runtime call failed";
+        case SPLC_EPLAN: return "call does not match the plan";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

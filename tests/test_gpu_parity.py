@@ -1,0 +1,135 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on seeded inputs spanning several chunks and ragged tails, every
+source mode, both quantiser modes, both selection algorithms, and the
+degenerate cases (ties, zeros, constant chunks, denormals, kappa >= n_c)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_02360_amd import binding as B
+from paper_2601_02360_amd import workloads as W
+
+import parity
+
+pytestmark = pytest.mark.gpu
+
+RAGGED = [4096 * 5, 4096 * 3 + 17, 100, 4096, 1, 2047, 4096 * 2 + 4, 0, 4096 * 2 - 1]
+
+
+def gaussian_case(numels, R, seed, direct=None, heavy=False):
+    rng = np.random.default_rng(seed)
+    draw = (lambda n: rng.standard_t(3, n)) if heavy else (lambda n: rng.standard_normal(n))
+    th = [(rng.standard_normal(n) * 0.02).astype(np.float32) for n in numels]
+    ef = [[(rng.standard_normal(n) * 1e-4).astype(np.float32) for n in numels] for _ in range(R)]
+    deltas = [[(draw(n) * 1e-3).astype(np.float32) for n in numels] for _ in range(R)]
+    if direct is None:
+        tl = [[(th[t] - deltas[r][t]).astype(np.float32) for t in range(len(numels))] for r in range(R)]
+        return parity.HostCase(th, ef, theta_local=tl)
+    if direct == "bf16":
+        deltas = [[(d.view(np.uint32) >> 16).astype(np.uint16) for d in r] for r in deltas]
+    return parity.HostCase(th, ef, delta=deltas)
+
+
+@pytest.mark.parametrize("select", [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX])
+@pytest.mark.parametrize("kappa", [1, 32, 64, 128, 256, 300, 4096])
+def test_ragged_tensor_list_params_mode(kappa, select):
+    case = gaussian_case(RAGGED, R=3, seed=kappa)
+    parity.check(case, kappa, select=select, what="ragged kappa=%d" % kappa)
+
+
+@pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("direct", ["f32", "bf16"])
+def test_direct_modes_and_identity_quantiser(direct, quant):
+    case = gaussian_case(RAGGED, R=2, seed=17, direct=direct, heavy=True)
+    parity.check(case, 64, quant=quant, what="direct %s quant=%s" % (direct, quant))
+
+
+@pytest.mark.parametrize("quant", [True, False])
+def test_identity_quantiser_params_mode_two_steps(quant):
+    case = gaussian_case([4096 * 4 + 5, 777], R=4, seed=5)
+    parity.check(case, 32, lr=0.8, quant=quant, outer_steps=2, what="two steps")
+
+
+@pytest.mark.parametrize("select", [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX])
+def test_ties_zeros_and_constant_chunks(select):
+    rng = np.random.default_rng(3)
+    n_chunks = 12
+    n = 4096 * n_chunks + 1000
+    x = np.zeros(n, np.float32)
+    few = np.array([0.0, -0.0, 0.5, -0.5, 1.0, -1.0, 2.0, 3.0, -3.0], np.float32)
+    x[:4096 * 4] = few[rng.integers(0, len(few), 4096 * 4)]           # few distinct magnitudes: ties everywhere
+    x[4096 * 4:4096 * 5] = 0.0                                          # all zero
+    x[4096 * 5:4096 * 6] = -7.25                                        # constant: 4096-way tie
+    x[4096 * 6:4096 * 7] = 0.0
+    x[4096 * 6 + np.array([5, 900, 4000])] = [1.0, -2.0, 3.0]           # fewer non-zeros than kappa
+    x[4096 * 7:4096 * 8] = np.array([1, 2, 3, 0x7FFFFF] * 1024, np.uint32).view(np.float32)   # subnormals
+    x[4096 * 8:4096 * 9] = (rng.integers(0, 3, 4096) * 0.125).astype(np.float32)              # ~1365-way ties
+    x[4096 * 9:] = (rng.standard_normal(n - 4096 * 9) * 1e-3).astype(np.float32)
+    # bf16-rounded values and a zero mask: ties at the threshold are common
+    y = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    y = ((y.view(np.uint32) >> 16) << 16).view(np.float32) * (rng.random(n) < 0.5)
+    th = [np.zeros(n, np.float32), np.zeros(n, np.float32)]
+    ef = [[np.zeros(n, np.float32), np.zeros(n, np.float32)] for _ in range(2)]
+    deltas = [[x, y.astype(np.float32)], [y.astype(np.float32), x]]
+    case = parity.HostCase(th, ef, delta=deltas)
+    for kappa in (1, 32, 64, 200):
+        parity.check(case, kappa, beta=1.0, select=select, what="ties kappa=%d" % kappa)
+
+
+def test_workload0_full():
+    cfg = W.WORKLOADS[0]
+    rs = W.ReplicaSet(0, device="cuda")
+    case = parity.HostCase([parity.to_np(t) for t in rs.theta_outer],
+                           [[parity.to_np(t) for t in r] for r in rs.ef],
+                           theta_local=[[parity.to_np(t) for t in r] for r in rs.theta_local])
+    parity.check(case, cfg["kappa"], cfg["beta"], cfg["outer_lr"], what="workload 0")
+
+
+def test_workload1_layer_subset_all_replicas():
+    """One transformer layer, the final norm and a slice-free embedding of the ~150M set, R = 8."""
+    cfg = W.WORKLOADS[1]
+    tensors = list(range(9)) + [108, 109]
+    rs = W.ReplicaSet(1, device="cuda", tensors=tensors)
+    case = parity.HostCase([parity.to_np(t) for t in rs.theta_outer],
+                           [[parity.to_np(t) for t in r] for r in rs.ef],
+                           theta_local=[[parity.to_np(t) for t in r] for r in rs.theta_local])
+    parity.check(case, cfg["kappa"], cfg["beta"], cfg["outer_lr"], what="workload 1 subset")
+
+
+def test_same_inputs_twice_give_identical_bytes():
+    case = gaussian_case([4096 * 9 + 3], R=5, seed=23)
+    a = parity.run_gpu(case, 64, 0.95, 1.0)
+    b = parity.run_gpu(case, 64, 0.95, 1.0)
+    for key in ("pairs", "aux"):
+        for x, y in zip(a[0][key], b[0][key]):
+            assert x.tobytes() == y.tobytes()
+    for x, y in zip(a[0]["dbar"] + a[0]["theta"], b[0]["dbar"] + b[0]["theta"]):
+        assert x.tobytes() == y.tobytes()
+
+
+def test_runs_on_a_side_stream():
+    case = gaussian_case([4096 * 3 + 9, 50], R=2, seed=29)
+    want = parity.run_oracle(case, 32, 0.95, 1.0)
+    s = torch.cuda.Stream()
+    got = parity.run_gpu(case, 32, 0.95, 1.0, stream=s)
+    parity.compare(got, want, "side stream")
+
+
+def test_error_returns_do_not_launch():
+    plan = B.Plan([4096, 10], 32)
+    e = [torch.zeros(4096, device="cuda"), torch.zeros(10, device="cuda")]
+    p, a = plan.message_buffers()
+    with pytest.raises(B.SparseLoCoError) as ei:
+        B.sparseloco_compress(plan, e, p, a, 0.95, theta_outer=e, theta_local=[e[0], None])
+    assert ei.value.status == B.SPLC_EINVAL
+    big = torch.zeros(4096 + 8, device="cuda")
+    with pytest.raises(B.SparseLoCoError) as ei:
+        B.sparseloco_compress(plan, [big[1:4097], e[1]], p, a, 0.95, delta=e)
+    assert ei.value.status == B.SPLC_EALIGN
+    with pytest.raises(B.SparseLoCoError) as ei:
+        B.sparseloco_compress(plan, e, p, a, float("inf"), delta=e)
+    assert ei.value.status == B.SPLC_EINVAL
+    with pytest.raises(B.SparseLoCoError) as ei:
+        B.sparseloco_aggregate(plan, [], [], e)
+    assert ei.value.status == B.SPLC_EINVAL
+    plan.close()
