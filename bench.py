@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the SparseLoCo outer step (paper section 2.1) on one MI355X.
+
+One "step" = one full outer step over the whole parameter set: R x compress
+(one per simulated replica) + 1 x aggregate + 1 x outer update, all inputs
+resident in HBM.  Metric: parameters per second of outer step
+(N_params / time per step), plus the HBM-roofline position of the dominant
+kernel (compress) from HIP-event timings of every launch, and the CPU oracle
+timed on a bounded sample of the same workload on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu]
+
+Prints ONE JSON line on stdout; a per-kernel breakdown goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak, GB/s
+
+
+def algorithmic_bytes(n_params, n_chunks, kappa, R, direct_bf16):
+    """Bytes the method itself must move at the three-call boundary (per launch)."""
+    payload = n_chunks * (2 * kappa + 8)
+    compress = (10 if direct_bf16 else 16) * n_params + payload      # theta_o, theta_l, e in, e out (+ message)
+    aggregate = R * payload + 4 * n_params                           # messages in, dense mean out
+    update = 12 * n_params                                           # theta in/out, mean in
+    return compress, aggregate, update
+
+
+def read_traffic(workload_name):
+    """HBM bytes per compress launch measured with rocprofv3 --pmc (profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "compress_%s_hbm_traffic.txt" % workload_name)
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(rs, cfg, sample_tensors):
+    """The oracle, as it stands, on the host cores: one full outer step (R x compress +
+    aggregate + update) over a fixed tensor subset of the same workload."""
+    import numpy as np
+    import torch
+    import oracle
+
+    def to_np(t):
+        t = t.detach().cpu().contiguous()
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).numpy().view(np.uint16)
+        return t.numpy()
+    th = [to_np(rs.theta_outer[i]) for i in sample_tensors]
+    numels = [int(x.size) for x in th]
+    ef = [[to_np(rs.ef[r][i]).copy() for i in sample_tensors] for r in range(rs.R)]
+    if rs.direct:
+        src = [[to_np(rs.delta[r][i]) for i in sample_tensors] for r in range(rs.R)]
+    else:
+        src = [[to_np(rs.theta_local[r][i]) for i in sample_tensors] for r in range(rs.R)]
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+    oracle.set_threads(threads)
+    t0 = time.perf_counter()
+    pairs, aux = [], []
+    for r in range(rs.R):
+        if rs.direct:
+            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], delta=src[r])
+        else:
+            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], theta_outer=th, theta_local=src[r])
+        pairs.append(p), aux.append(a)
+    dbar = oracle.aggregate(numels, pairs, aux, cfg["kappa"])
+    oracle.outer_update(th, dbar, cfg["outer_lr"])
+    dt = time.perf_counter() - t0
+    n = sum(numels)
+    return {"value": n / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "sample": "one full outer step (R=%d compress + aggregate + update) over %d tensors / %d params "
+                      "of the same workload (its first tensors in list order), %.1f s" % (rs.R, len(numels), n, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=2)
+    ap.add_argument("--kappa", type=int, default=None)
+    ap.add_argument("--replicas", type=int, default=None)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference point for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_02360_amd import binding as B
+    from paper_2601_02360_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    cfg = dict(W.WORKLOADS[args.workload])
+    if args.kappa:
+        cfg["kappa"] = args.kappa
+    R = args.replicas or cfg["replicas"]
+    t_gen = time.perf_counter()
+    rs = W.ReplicaSet(args.workload, device="cuda", replicas=R)
+    torch.cuda.synchronize()
+    print("generated workload %d (%s): %d tensors, %d params, R=%d in %.1f s; %.1f GB allocated"
+          % (args.workload, cfg["name"], len(rs.numels), rs.num_params, R, time.perf_counter() - t_gen,
+             torch.cuda.memory_allocated() / 1e9), file=sys.stderr, flush=True)
+
+    plan = B.Plan(rs.numels, cfg["kappa"], True)
+    msgs = [plan.message_buffers() for _ in range(R)]
+    dbar = [torch.empty(n, device="cuda") for n in rs.numels]
+    t_theta = B.ptr_table(rs.theta_outer)
+    t_dbar = B.ptr_table(dbar)
+    t_ef = [B.ptr_table(rs.ef[r]) for r in range(R)]
+    t_src = [B.ptr_table(rs.delta[r] if rs.direct else rs.theta_local[r]) for r in range(R)]
+    t_pairs = B.ptr_table([m[0] for m in msgs])
+    t_aux = B.ptr_table([m[1] for m in msgs])
+    stream = torch.cuda.current_stream()
+
+    ev_c = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(R)]
+            for _ in range(args.steps)]
+    ev_a = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            for _ in range(args.steps)]
+
+    def step(k=None):
+        for r in range(R):
+            if k is not None:
+                ev_c[k][r][0].record(stream)
+            if rs.direct:
+                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], delta=t_src[r],
+                                      delta_dtype=B.SPLC_BF16, stream=stream)
+            else:
+                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], theta_outer=t_theta,
+                                      theta_local=t_src[r], stream=stream)
+            if k is not None:
+                ev_c[k][r][1].record(stream)
+        if k is not None:
+            ev_a[k][0].record(stream)
+        B.sparseloco_aggregate(plan, t_pairs, t_aux, t_dbar, stream=stream)
+        if k is not None:
+            ev_a[k][1].record(stream)
+        B.sparseloco_outer_update(plan, t_theta, t_dbar, cfg["outer_lr"], stream=stream)
+        if k is not None:
+            ev_a[k][2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    ms_step = 1e3 * elapsed / args.steps
+    n = rs.num_params
+    nch = plan.num_chunks
+    b_c, b_a, b_u = algorithmic_bytes(n, nch, cfg["kappa"], R, rs.direct)
+    ms_c = [a.elapsed_time(b) for row in ev_c for a, b in row]
+    ms_a = [e[0].elapsed_time(e[1]) for e in ev_a]
+    ms_u = [e[1].elapsed_time(e[2]) for e in ev_a]
+    avg = lambda xs: sum(xs) / len(xs)
+    gbs = lambda b, ms: b / (ms * 1e-3) / 1e9
+    ach = gbs(b_c, avg(ms_c))
+    total_bytes = R * b_c + b_a + b_u
+    print("per launch: compress %.3f ms (%.0f GB/s algorithmic), aggregate %.3f ms (%.0f GB/s), update %.3f ms "
+          "(%.0f GB/s); whole step %.3f ms = %.0f GB/s algorithmic = %.1f %% of HBM peak"
+          % (avg(ms_c), ach, avg(ms_a), gbs(b_a, avg(ms_a)), avg(ms_u), gbs(b_u, avg(ms_u)), ms_step,
+             gbs(total_bytes, ms_step), 100 * gbs(total_bytes, ms_step) / HBM_PEAK_GBS), file=sys.stderr, flush=True)
+
+    result = {
+        "metric": "outer-step params/sec (compress+aggregate+update)",
+        "value": n / (ms_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d tensors, %d params, kappa=%d per 4096-chunk, R=%d replicas, beta=%g, "
+                               "2-bit quantiser, outer_lr=%g" % (cfg["name"], len(rs.numels), n, cfg["kappa"], R,
+                                                                 cfg["beta"], cfg["outer_lr"]),
+                   "n_params": n, "n_chunks": nch, "kappa": cfg["kappa"], "replicas": R,
+                   "step_algorithmic_bytes": total_bytes,
+                   "step_frac_of_hbm_peak": gbs(total_bytes, ms_step) / HBM_PEAK_GBS,
+                   "kernel_ms": {"compress": avg(ms_c), "aggregate": avg(ms_a), "outer_update": avg(ms_u)}},
+        "roofline": {"bound": "hbm", "kernel": "compress_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": read_traffic(cfg["name"]),
+                     "algorithmic_bytes_per_launch": b_c},
+    }
+    if not args.no_cpu:
+        sample = [i for i in range(min(54, len(rs.numels)))]
+        result["cpu_baseline"] = cpu_baseline(rs, cfg, sample)
+    plan.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
