@@ -27,9 +27,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E peak, GB/s
 
 
-def algorithmic_bytes(n_params, n_chunks, kappa, R, direct_bf16):
+def algorithmic_bytes(n_params, n_chunks, kappa, R, direct_bf16, quant=True):
     """Bytes the method itself must move at the three-call boundary (per launch)."""
-    payload = n_chunks * (2 * kappa + 8)
+    payload = n_chunks * (2 * kappa + 8) if quant else n_chunks * 6 * kappa
     compress = (10 if direct_bf16 else 16) * n_params + payload      # theta_o, theta_l, e in, e out (+ message)
     aggregate = R * payload + 4 * n_params                           # messages in, dense mean out
     update = 12 * n_params                                           # theta in/out, mean in
@@ -46,7 +46,7 @@ def read_traffic(workload_name):
         return None
 
 
-def cpu_baseline(rs, cfg, sample_tensors):
+def cpu_baseline(rs, cfg, sample_tensors, quant=True):
     """The oracle, as it stands, on the host cores: one full outer step (R x compress +
     aggregate + update) over a fixed tensor subset of the same workload."""
     import numpy as np
@@ -71,11 +71,12 @@ def cpu_baseline(rs, cfg, sample_tensors):
     pairs, aux = [], []
     for r in range(rs.R):
         if rs.direct:
-            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], delta=src[r])
+            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], delta=src[r], quant=quant)
         else:
-            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], theta_outer=th, theta_local=src[r])
+            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], theta_outer=th, theta_local=src[r],
+                                   quant=quant)
         pairs.append(p), aux.append(a)
-    dbar = oracle.aggregate(numels, pairs, aux, cfg["kappa"])
+    dbar = oracle.aggregate(numels, pairs, aux, cfg["kappa"], quant=quant)
     oracle.outer_update(th, dbar, cfg["outer_lr"])
     dt = time.perf_counter() - t0
     n = sum(numels)
@@ -92,6 +93,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--kappa", type=int, default=None)
     ap.add_argument("--replicas", type=int, default=None)
+    ap.add_argument("--quant", choices=["2bit", "none"], default="2bit",
+                    help="2bit: sign + one magnitude bit (default); none: Q = identity, fp32 values in the message")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for rocprofv3 --pmc byte counters)")
@@ -120,7 +123,8 @@ def main():
           % (args.workload, cfg["name"], len(rs.numels), rs.num_params, R, time.perf_counter() - t_gen,
              torch.cuda.memory_allocated() / 1e9), file=sys.stderr, flush=True)
 
-    plan = B.Plan(rs.numels, cfg["kappa"], True)
+    quant = args.quant == "2bit"
+    plan = B.Plan(rs.numels, cfg["kappa"], quant)
     msgs = [plan.message_buffers() for _ in range(R)]
     dbar = [torch.empty(n, device="cuda") for n in rs.numels]
     t_theta = B.ptr_table(rs.theta_outer)
@@ -157,6 +161,27 @@ def main():
         if k is not None:
             ev_a[k][2].record(stream)
 
+    def fused_step():
+        for r in range(R):
+            if rs.direct:
+                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], delta=t_src[r],
+                                      delta_dtype=B.SPLC_BF16, stream=stream)
+            else:
+                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], theta_outer=t_theta,
+                                      theta_local=t_src[r], stream=stream)
+        B.sparseloco_aggregate_update(plan, t_pairs, t_aux, t_theta, cfg["outer_lr"], stream=stream)
+
+    # the same outer step with line 5 in one pass (sparseloco_aggregate_update, no dense mean written):
+    # reported beside the headline, which stays at the three-call boundary
+    for _ in range(args.warmup):
+        fused_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fused_step()
+    torch.cuda.synchronize()
+    ms_fused = 1e3 * (time.perf_counter() - t0) / args.steps
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -176,7 +201,7 @@ def main():
     ms_step = 1e3 * elapsed / args.steps
     n = rs.num_params
     nch = plan.num_chunks
-    b_c, b_a, b_u = algorithmic_bytes(n, nch, cfg["kappa"], R, rs.direct)
+    b_c, b_a, b_u = algorithmic_bytes(n, nch, cfg["kappa"], R, rs.direct, quant)
     ms_c = [a.elapsed_time(b) for row in ev_c for a, b in row]
     ms_a = [e[0].elapsed_time(e[1]) for e in ev_a]
     ms_u = [e[1].elapsed_time(e[2]) for e in ev_a]
@@ -188,6 +213,8 @@ def main():
           "(%.0f GB/s); whole step %.3f ms = %.0f GB/s algorithmic = %.1f %% of HBM peak"
           % (avg(ms_c), ach, avg(ms_a), gbs(b_a, avg(ms_a)), avg(ms_u), gbs(b_u, avg(ms_u)), ms_step,
              gbs(total_bytes, ms_step), 100 * gbs(total_bytes, ms_step) / HBM_PEAK_GBS), file=sys.stderr, flush=True)
+    print("with aggregate+update fused (sparseloco_aggregate_update): %.3f ms per step" % ms_fused,
+          file=sys.stderr, flush=True)
 
     result = {
         "metric": "outer-step params/sec (compress+aggregate+update)",
@@ -203,19 +230,21 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "%s: %d tensors, %d params, kappa=%d per 4096-chunk, R=%d replicas, beta=%g, "
-                               "2-bit quantiser, outer_lr=%g" % (cfg["name"], len(rs.numels), n, cfg["kappa"], R,
-                                                                 cfg["beta"], cfg["outer_lr"]),
+                               "%s, outer_lr=%g" % (cfg["name"], len(rs.numels), n, cfg["kappa"], R, cfg["beta"],
+                                                     "2-bit quantiser" if quant else "Q = identity (fp32 values)",
+                                                     cfg["outer_lr"]),
                    "n_params": n, "n_chunks": nch, "kappa": cfg["kappa"], "replicas": R,
                    "step_algorithmic_bytes": total_bytes,
                    "step_frac_of_hbm_peak": gbs(total_bytes, ms_step) / HBM_PEAK_GBS,
-                   "kernel_ms": {"compress": avg(ms_c), "aggregate": avg(ms_a), "outer_update": avg(ms_u)}},
+                   "kernel_ms": {"compress": avg(ms_c), "aggregate": avg(ms_a), "outer_update": avg(ms_u)},
+                   "fused_line5_ms_per_step": ms_fused, "fused_line5_params_per_s": n / (ms_fused * 1e-3)},
         "roofline": {"bound": "hbm", "kernel": "compress_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": read_traffic(cfg["name"]),
                      "algorithmic_bytes_per_launch": b_c},
     }
     if not args.no_cpu:
         sample = [i for i in range(min(54, len(rs.numels)))]
-        result["cpu_baseline"] = cpu_baseline(rs, cfg, sample)
+        result["cpu_baseline"] = cpu_baseline(rs, cfg, sample, quant)
     plan.close()
     print(json.dumps(result), flush=True)
 

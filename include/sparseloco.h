@@ -140,6 +140,17 @@ int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas,
 int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer,
                             const float* const* delta_bar, float outer_lr, void* stream);
 
+/*
+ * Line 5 in one pass: the mean as in sparseloco_aggregate and the update as in
+ * sparseloco_outer_update, bit-identical to calling the two in sequence, without
+ * the round trip of delta_bar through memory.  theta_outer[n_tensors] is updated
+ * in place.  delta_bar_out may be NULL; if given, the dense mean is written too.
+ */
+int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas,
+                                const uint16_t* const* pairs, const float* const* aux,
+                                float* const* theta_outer, float outer_lr,
+                                float* const* delta_bar_out, void* stream);
+
 const char* sparseloco_strerror(int status);
 
 #ifdef __cplusplus

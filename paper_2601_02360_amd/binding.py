@@ -27,7 +27,7 @@ EXPORTS = [
     "sparseloco_plan_create", "sparseloco_plan_destroy", "sparseloco_plan_num_chunks",
     "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
     "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
-    "sparseloco_outer_update", "sparseloco_strerror",
+    "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_strerror",
 ]
 
 _lib = None
@@ -68,6 +68,8 @@ def lib():
         L.sparseloco_aggregate.argtypes = [vp, i32, pp, pp, pp, vp]
         L.sparseloco_outer_update.restype = i32
         L.sparseloco_outer_update.argtypes = [vp, pp, pp, f32, vp]
+        L.sparseloco_aggregate_update.restype = i32
+        L.sparseloco_aggregate_update.argtypes = [vp, i32, pp, pp, pp, f32, pp, vp]
         L.sparseloco_strerror.restype = ctypes.c_char_p
         L.sparseloco_strerror.argtypes = [i32]
         _lib = L
@@ -175,3 +177,14 @@ def sparseloco_outer_update(plan: Plan, theta_outer, delta_bar, outer_lr: float,
                                        _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_outer_update")
+
+
+def sparseloco_aggregate_update(plan: Plan, pairs, aux, theta_outer, outer_lr: float, *, delta_bar_out=None,
+                                stream=None) -> None:
+    """Mean over replicas and outer update in one pass (theta_outer in place); delta_bar_out optional."""
+    pt, at = _table(pairs), _table(aux)
+    rc = lib().sparseloco_aggregate_update(plan.handle, len(pt), pt, at, _table(theta_outer), float(outer_lr),
+                                           None if delta_bar_out is None else _table(delta_bar_out),
+                                           _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_aggregate_update")

@@ -423,57 +423,147 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
     }
 }
 
-// Line 5, first half: mean over replicas.  One workgroup per chunk; a dense fp32
-// accumulator of the chunk lives in LDS.  Replicas are applied one after the
-// other with a barrier in between; inside one replica the indices are distinct,
-// so every element sees its addends in ascending replica order.
-template <int QUANT>
-__global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __restrict__ chunks, int n_replicas,
-                                                             uint32_t kappa,
-                                                             const uint16_t* const* __restrict__ pairs_tab,
-                                                             const float* const* __restrict__ aux_tab,
-                                                             float* const* __restrict__ out_tab) {
-    __shared__ __align__(16) float acc[kChunk];
-    const int tid = threadIdx.x;
-    const uint64_t c = blockIdx.x;
-    const ChunkDesc d = chunks[c];
-    const uint32_t n_c = d.n_c;
-    const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
-    float4* acc4 = reinterpret_cast<float4*>(acc);
+// Line 5, first half: sum of the decoded messages of one chunk into a dense LDS accumulator.
+// Executed by ONE wave: LDS operations of a wave complete in program order, so the add of
+// replica r+1 at some index sees the add of replica r at the same index without a barrier, and
+// inside one replica the indices are distinct.  Every element therefore receives its addends in
+// ascending replica order -- deterministic, no float atomics, no sort.  Messages are fetched in
+// batches of eight replicas so that the global loads of a batch are in flight together.
+template <int QUANT, int KP>
+__device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_t n_c, uint32_t kappa,
+                                                 uint32_t kappa_c, int n_replicas,
+                                                 const uint16_t* const* __restrict__ pairs_tab,
+                                                 const float* const* __restrict__ aux_tab, int lane) {
+    constexpr int kBatch = 8;
+    for (int r0 = 0; r0 < n_replicas; r0 += kBatch) {
+        uint32_t p[kBatch][KP];
+        float lo[kBatch], hi[kBatch], val[kBatch][KP];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) acc4[s * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
-    __syncthreads();
+        for (int i = 0; i < kBatch; ++i) {
+            lo[i] = hi[i] = 0.f;
+            if (r0 + i < n_replicas) {
+                const uint16_t* pr = pairs_tab[r0 + i] + c * kappa;
+                const float* ar = aux_tab[r0 + i];
+                if (QUANT == SPLC_QUANT_2BIT) {
+                    lo[i] = ar[2 * c];
+                    hi[i] = ar[2 * c + 1];
+                }
+#pragma unroll
+                for (int k = 0; k < KP; ++k) {
+                    const uint32_t t = lane + 64 * k;
+                    p[i][k] = t < kappa_c ? (uint32_t)pr[t] : 0xFFFFu;
+                    val[i][k] = (QUANT == SPLC_QUANT_NONE && t < kappa_c) ? ar[c * kappa + t] : 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            if (r0 + i < n_replicas) {
+#pragma unroll
+                for (int k = 0; k < KP; ++k) {
+                    const uint32_t t = lane + 64 * k;
+                    const uint32_t idx = p[i][k] & 0xFFFu;
+                    float q;
+                    if (QUANT == SPLC_QUANT_2BIT) {
+                        const float level = (p[i][k] & 0x1000u) ? hi[i] : lo[i];
+                        q = (p[i][k] & 0x2000u) ? -level : level;
+                    } else {
+                        q = val[i][k];
+                    }
+                    if (t < kappa_c && idx < n_c) acc[idx] = __fadd_rn(acc[idx], q);
+                }
+            }
+        }
+    }
+}
+
+// Any kappa: one replica after the other, no batching (used for kappa > 256).
+template <int QUANT>
+__device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uint32_t n_c, uint32_t kappa,
+                                                     uint32_t kappa_c, int n_replicas,
+                                                     const uint16_t* const* __restrict__ pairs_tab,
+                                                     const float* const* __restrict__ aux_tab, int lane) {
     for (int r = 0; r < n_replicas; ++r) {
         const uint16_t* pr = pairs_tab[r] + c * kappa;
         const float* ar = aux_tab[r];
         float lo = 0.f, hi = 0.f;
         if (QUANT == SPLC_QUANT_2BIT) { lo = ar[2 * c]; hi = ar[2 * c + 1]; }
-        for (uint32_t t = tid; t < kappa_c; t += kThreads) {
-            uint32_t p = pr[t];
-            uint32_t idx = p & 0xFFFu;
+        for (uint32_t t = lane; t < kappa_c; t += 64) {
+            const uint32_t p = pr[t];
+            const uint32_t idx = p & 0xFFFu;
             float q;
             if (QUANT == SPLC_QUANT_2BIT) {
-                float level = (p & 0x1000u) ? hi : lo;
+                const float level = (p & 0x1000u) ? hi : lo;
                 q = (p & 0x2000u) ? -level : level;
             } else {
                 q = ar[c * kappa + t];
             }
             if (idx < n_c) acc[idx] = __fadd_rn(acc[idx], q);
         }
-        __syncthreads();
     }
+}
+
+// Line 5 of the update equations.  One workgroup per chunk; all lanes clear the 16 KB LDS
+// accumulator, wave 0 applies the messages, all lanes divide once by M and write.
+//   UPDATE = 0: delta_bar = acc / M is written densely (sparseloco_aggregate).
+//   UPDATE = 1: theta = fl(theta - fl(eta * delta_bar)) is applied in the same pass; delta_bar is
+//               written only if a table for it is given (sparseloco_aggregate_update).
+template <int QUANT, int UPDATE>
+__global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __restrict__ chunks, int n_replicas,
+                                                             uint32_t kappa,
+                                                             const uint16_t* const* __restrict__ pairs_tab,
+                                                             const float* const* __restrict__ aux_tab,
+                                                             float* const* __restrict__ dbar_tab,
+                                                             float* const* __restrict__ theta_tab, float eta) {
+    __shared__ __align__(16) float acc[kChunk];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint64_t c = blockIdx.x;
+    const ChunkDesc d = chunks[c];
+    const uint32_t n_c = d.n_c;
+    const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
+    const bool full = n_c == (uint32_t)kChunk;
+    float4* acc4 = reinterpret_cast<float4*>(acc);
+    float* th = UPDATE ? theta_tab[d.tensor] + d.offset : nullptr;
+    float* po = dbar_tab ? dbar_tab[d.tensor] + d.offset : nullptr;
+    float4 tv[4];
+    if (UPDATE && full) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) tv[s] = stream_load(reinterpret_cast<const float4*>(th) + s * kThreads + tid);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) acc4[s * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+    if (wave == 0) {
+        if (kappa_c <= 64) accumulate_chunk<QUANT, 1>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        else if (kappa_c <= 128) accumulate_chunk<QUANT, 2>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        else if (kappa_c <= 256) accumulate_chunk<QUANT, 4>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        else accumulate_chunk_any<QUANT>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+    }
+    __syncthreads();
     const float m = (float)n_replicas;
-    float* po = out_tab[d.tensor] + d.offset;
-    if (n_c == (uint32_t)kChunk) {
-        float4* po4 = reinterpret_cast<float4*>(po);
+    if (full) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             float4 v = acc4[s * kThreads + tid];
             v.x = __fdiv_rn(v.x, m); v.y = __fdiv_rn(v.y, m); v.z = __fdiv_rn(v.z, m); v.w = __fdiv_rn(v.w, m);
-            stream_store(po4 + s * kThreads + tid, v);
+            if (po) stream_store(reinterpret_cast<float4*>(po) + s * kThreads + tid, v);
+            if (UPDATE) {
+                float4 t = tv[s];
+                t.x = __fsub_rn(t.x, __fmul_rn(eta, v.x));
+                t.y = __fsub_rn(t.y, __fmul_rn(eta, v.y));
+                t.z = __fsub_rn(t.z, __fmul_rn(eta, v.z));
+                t.w = __fsub_rn(t.w, __fmul_rn(eta, v.w));
+                stream_store(reinterpret_cast<float4*>(th) + s * kThreads + tid, t);
+            }
         }
     } else {
-        for (uint32_t idx = tid; idx < n_c; idx += kThreads) po[idx] = __fdiv_rn(acc[idx], m);
+        for (uint32_t idx = tid; idx < n_c; idx += kThreads) {
+            const float v = __fdiv_rn(acc[idx], m);
+            if (po) po[idx] = v;
+            if (UPDATE) th[idx] = __fsub_rn(th[idx], __fmul_rn(eta, v));
+        }
     }
 }
 
@@ -611,8 +701,7 @@ int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* 
         }
     }
     int rc = SPLC_OK;
-    size_t n_ptrs = (size_t)3 * (size_t)n_tensors;
-    if (n_ptrs < (size_t)n_tensors + 2 * (size_t)kMaxReplicas) n_ptrs = (size_t)n_tensors + 2 * (size_t)kMaxReplicas;
+    const size_t n_ptrs = 3 * (size_t)n_tensors + 2 * (size_t)kMaxReplicas;      // largest table of any call
     plan->slot_bytes = (n_ptrs * sizeof(void*) + 255) & ~(size_t)255;
     if (n_chunks > 0 &&
         hipMalloc(reinterpret_cast<void**>(&plan->d_chunks), (size_t)n_chunks * sizeof(ChunkDesc)) != hipSuccess)
@@ -728,18 +817,27 @@ int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype, co
     return slot_release(plan, slot, st);
 }
 
-int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
-                         const float* const* aux, float* const* delta_bar_out, void* stream) {
-    if (!plan || !pairs || !aux || !delta_bar_out) return SPLC_EINVAL;
+static int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
+                          const float* const* aux, float* const* delta_bar_out, float* const* theta_outer,
+                          float outer_lr, bool update, void* stream) {
+    if (!plan || !pairs || !aux) return SPLC_EINVAL;
+    if (update ? !theta_outer : !delta_bar_out) return SPLC_EINVAL;
     if (n_replicas < 1 || n_replicas > kMaxReplicas) return SPLC_EINVAL;
+    if (!(outer_lr == outer_lr) || outer_lr - outer_lr != 0.f) return SPLC_EINVAL;
     for (int r = 0; r < n_replicas; ++r) {
         if (!pairs[r] || !aux[r]) return SPLC_EINVAL;
         if (!aligned(pairs[r], 2) || !aligned(aux[r], 4)) return SPLC_EALIGN;
     }
     for (int i = 0; i < plan->n_tensors; ++i) {
         if (plan->numel[i] == 0) continue;
-        if (!delta_bar_out[i]) return SPLC_EINVAL;
-        if (!aligned(delta_bar_out[i], 16)) return SPLC_EALIGN;
+        if (delta_bar_out) {
+            if (!delta_bar_out[i]) return SPLC_EINVAL;
+            if (!aligned(delta_bar_out[i], 16)) return SPLC_EALIGN;
+        }
+        if (update) {
+            if (!theta_outer[i]) return SPLC_EINVAL;
+            if (!aligned(theta_outer[i], 16)) return SPLC_EALIGN;
+        }
     }
     int rc = check_device(plan);
     if (rc != SPLC_OK) return rc;
@@ -755,20 +853,45 @@ int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas, const uint16_t* 
         tab[r] = const_cast<uint16_t*>(pairs[r]);
         tab[nr + r] = const_cast<float*>(aux[r]);
     }
-    for (size_t i = 0; i < nt; ++i) tab[2 * nr + i] = delta_bar_out[i];
+    for (size_t i = 0; i < nt; ++i) {
+        tab[2 * nr + i] = delta_bar_out ? delta_bar_out[i] : nullptr;
+        tab[2 * nr + nt + i] = update ? theta_outer[i] : nullptr;
+    }
     char* dtab;
-    if ((rc = slot_upload(plan, slot, (2 * nr + nt) * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
+    if ((rc = slot_upload(plan, slot, (2 * nr + 2 * nt) * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
     const uint16_t* const* dp = reinterpret_cast<const uint16_t* const*>(dtab);
     const float* const* dx = reinterpret_cast<const float* const*>(dtab + nr * sizeof(void*));
-    float* const* dout = reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*));
-    if (plan->quant == SPLC_QUANT_2BIT)
-        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_2BIT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0,
-                           st, plan->d_chunks, n_replicas, (uint32_t)plan->kappa, dp, dx, dout);
+    float* const* dout =
+        delta_bar_out ? reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*)) : nullptr;
+    float* const* dth = reinterpret_cast<float* const*>(dtab + (2 * nr + nt) * sizeof(void*));
+    const dim3 grid((unsigned)plan->n_chunks), block(kThreads);
+    const uint32_t kappa = (uint32_t)plan->kappa;
+    const bool q2 = plan->quant == SPLC_QUANT_2BIT;
+    if (q2 && !update)
+        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_2BIT, 0>), grid, block, 0, st, plan->d_chunks, n_replicas,
+                           kappa, dp, dx, dout, dth, outer_lr);
+    else if (q2)
+        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_2BIT, 1>), grid, block, 0, st, plan->d_chunks, n_replicas,
+                           kappa, dp, dx, dout, dth, outer_lr);
+    else if (!update)
+        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_NONE, 0>), grid, block, 0, st, plan->d_chunks, n_replicas,
+                           kappa, dp, dx, dout, dth, outer_lr);
     else
-        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_NONE>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0,
-                           st, plan->d_chunks, n_replicas, (uint32_t)plan->kappa, dp, dx, dout);
+        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_NONE, 1>), grid, block, 0, st, plan->d_chunks, n_replicas,
+                           kappa, dp, dx, dout, dth, outer_lr);
     if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
     return slot_release(plan, slot, st);
+}
+
+int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
+                         const float* const* aux, float* const* delta_bar_out, void* stream) {
+    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, nullptr, 0.f, false, stream);
+}
+
+int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
+                                const float* const* aux, float* const* theta_outer, float outer_lr,
+                                float* const* delta_bar_out, void* stream) {
+    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, theta_outer, outer_lr, true, stream);
 }
 
 int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer, const float* const* delta_bar,

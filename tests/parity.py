@@ -79,7 +79,10 @@ def _dev(x: np.ndarray, bf16: bool = False) -> torch.Tensor:
 
 
 def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AUTO, outer_steps=1,
-            deltas_per_step=None, stream: Optional[torch.cuda.Stream] = None):
+            deltas_per_step=None, stream: Optional[torch.cuda.Stream] = None, fused=None):
+    """fused: None = aggregate then outer_update; "with_mean" / "no_mean" = sparseloco_aggregate_update
+    with / without the dense mean output (without it, the returned mean is recomputed by a separate
+    sparseloco_aggregate call, which the fused call must agree with anyway)."""
     plan = B.Plan(case.numels, kappa, quant)
     plan.set_select(select)
     th = [_dev(x) for x in case.theta_outer]
@@ -102,8 +105,15 @@ def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AU
                 else:
                     B.sparseloco_compress(plan, ef[r], p, a, beta, theta_outer=th, theta_local=tl[r])
             dbar = [torch.full((n,), float("nan"), device="cuda") for n in case.numels]
-            B.sparseloco_aggregate(plan, [m[0] for m in msgs], [m[1] for m in msgs], dbar)
-            B.sparseloco_outer_update(plan, th, dbar, lr)
+            if fused is None:
+                B.sparseloco_aggregate(plan, [m[0] for m in msgs], [m[1] for m in msgs], dbar)
+                B.sparseloco_outer_update(plan, th, dbar, lr)
+            elif fused == "with_mean":
+                B.sparseloco_aggregate_update(plan, [m[0] for m in msgs], [m[1] for m in msgs], th, lr,
+                                              delta_bar_out=dbar)
+            else:
+                B.sparseloco_aggregate_update(plan, [m[0] for m in msgs], [m[1] for m in msgs], th, lr)
+                B.sparseloco_aggregate(plan, [m[0] for m in msgs], [m[1] for m in msgs], dbar)
             torch.cuda.synchronize()
             out.append(dict(pairs=[to_np(m[0]) for m in msgs], aux=[to_np(m[1]) for m in msgs],
                             ef=[[to_np(x) for x in r] for r in ef], dbar=[to_np(x) for x in dbar],
@@ -131,8 +141,8 @@ def compare(got, want, what=""):
 
 
 def check(case: HostCase, kappa, beta=0.95, lr=1.0, quant=True, select=B.SPLC_SELECT_AUTO, outer_steps=1,
-          deltas_per_step=None, what=""):
+          deltas_per_step=None, what="", fused=None):
     want = run_oracle(case, kappa, beta, lr, quant, outer_steps, deltas_per_step)
-    got = run_gpu(case, kappa, beta, lr, quant, select, outer_steps, deltas_per_step)
+    got = run_gpu(case, kappa, beta, lr, quant, select, outer_steps, deltas_per_step, fused=fused)
     compare(got, want, what)
     return got, want

@@ -76,6 +76,30 @@ def test_ties_zeros_and_constant_chunks(select):
         parity.check(case, kappa, beta=1.0, select=select, what="ties kappa=%d" % kappa)
 
 
+@pytest.mark.parametrize("fused", ["with_mean", "no_mean"])
+@pytest.mark.parametrize("kappa,R,quant", [(32, 3, True), (64, 8, True), (128, 9, True), (200, 2, True),
+                                           (300, 5, True), (64, 17, False), (4096, 2, True)])
+def test_fused_aggregate_update(kappa, R, quant, fused):
+    case = gaussian_case(RAGGED, R=R, seed=100 + kappa + R)
+    parity.check(case, kappa, lr=0.8, quant=quant, fused=fused, outer_steps=2, what="fused %s" % fused)
+
+
+def test_colliding_indices_many_replicas():
+    """All replicas send (almost) the same indices: every accumulator entry gets R addends."""
+    rng = np.random.default_rng(77)
+    numels = [4096 * 3 + 100]
+    R = 33
+    shared = (rng.standard_normal(numels[0]) * 1e-3).astype(np.float32)
+    th = [np.zeros(numels[0], np.float32)]
+    ef = [[np.zeros(numels[0], np.float32)] for _ in range(R)]
+    deltas = [[(shared + (rng.standard_normal(numels[0]) * 1e-5).astype(np.float32)).astype(np.float32)]
+              for _ in range(R)]
+    case = parity.HostCase(th, ef, delta=deltas)
+    for kappa in (16, 64, 128):
+        parity.check(case, kappa, what="collisions kappa=%d" % kappa)
+        parity.check(case, kappa, fused="no_mean", what="collisions fused kappa=%d" % kappa)
+
+
 def test_workload0_full():
     cfg = W.WORKLOADS[0]
     rs = W.ReplicaSet(0, device="cuda")
