@@ -121,6 +121,21 @@ int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype,
                         uint16_t* pairs_out, float* aux_out, void* stream);
 
 /*
+ * Lines 1-4 for several replicas that share theta_outer and live on this GPU
+ * (the single-node simulation of M replicas): one launch, theta_outer read once
+ * per chunk instead of once per replica.  Per replica the result is bit-identical
+ * to sparseloco_compress in SPLC_DELTA_FROM_PARAMS mode.
+ *   theta_outer[n_tensors]; theta_local[r][n_tensors], ef[r][n_tensors] (host
+ *   arrays of host arrays of device pointers); pairs_out[r], aux_out[r]: replica
+ *   r's message buffers, sized as for sparseloco_compress.  1 <= n_replicas <= 64.
+ */
+int sparseloco_compress_batch(sparseloco_plan* plan, int n_replicas,
+                              const float* const* theta_outer,
+                              const float* const* const* theta_local,
+                              float* const* const* ef, float beta,
+                              uint16_t* const* pairs_out, float* const* aux_out, void* stream);
+
+/*
  * Line 5, first half: the mean over n_replicas (the paper's M) of the decoded
  * messages.  pairs[r], aux[r]: replica r's message as written by
  * sparseloco_compress with the same plan.  Per element the contributions are

@@ -27,7 +27,8 @@ EXPORTS = [
     "sparseloco_plan_create", "sparseloco_plan_destroy", "sparseloco_plan_num_chunks",
     "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
     "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
-    "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_strerror",
+    "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
+    "sparseloco_strerror",
 ]
 
 _lib = None
@@ -70,6 +71,8 @@ def lib():
         L.sparseloco_outer_update.argtypes = [vp, pp, pp, f32, vp]
         L.sparseloco_aggregate_update.restype = i32
         L.sparseloco_aggregate_update.argtypes = [vp, i32, pp, pp, pp, f32, pp, vp]
+        L.sparseloco_compress_batch.restype = i32
+        L.sparseloco_compress_batch.argtypes = [vp, i32, pp, ctypes.POINTER(pp), ctypes.POINTER(pp), f32, pp, pp, vp]
         L.sparseloco_strerror.restype = ctypes.c_char_p
         L.sparseloco_strerror.argtypes = [i32]
         _lib = L
@@ -188,3 +191,25 @@ def sparseloco_aggregate_update(plan: Plan, pairs, aux, theta_outer, outer_lr: f
                                            _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_aggregate_update")
+
+
+def ptr_table_2d(tables):
+    """Host array of host pointer tables (one ptr_table per replica)."""
+    tabs = [_table(t) for t in tables]
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    arr = (pp * len(tabs))(*[ctypes.cast(t, pp) for t in tabs])
+    arr._keepalive = tabs
+    return arr
+
+
+def sparseloco_compress_batch(plan: Plan, theta_outer, theta_local, ef, pairs_out, aux_out, beta: float, *,
+                              stream=None) -> None:
+    """Lines 1-4 for R replicas sharing theta_outer, one launch.  theta_local / ef: per replica a list of
+    tensors (or ptr_table), or a prebuilt ptr_table_2d; pairs_out / aux_out: per replica message buffers."""
+    tl = theta_local if isinstance(theta_local, ctypes.Array) and hasattr(theta_local, "_keepalive") \
+        else ptr_table_2d(theta_local)
+    e = ef if isinstance(ef, ctypes.Array) and hasattr(ef, "_keepalive") else ptr_table_2d(ef)
+    rc = lib().sparseloco_compress_batch(plan.handle, len(tl), _table(theta_outer), tl, e, float(beta),
+                                         _table(pairs_out), _table(aux_out), _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_compress_batch")

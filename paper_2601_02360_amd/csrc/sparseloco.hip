@@ -26,7 +26,8 @@ constexpr int kThreads = 256;            // one workgroup per chunk
 constexpr int kCandCap = 256;            // candidates the exact ranking handles (one per lane)
 constexpr int kFilterKappaMax = 256;     // the candidate filter needs kappa <= number of lanes
 constexpr int kSlots = 32;               // staging slots for pointer tables
-constexpr int kMaxReplicas = 1024;
+constexpr int kMaxReplicas = 1024;         // messages one aggregate call accepts
+constexpr int kMaxBatch = 64;              // replicas one compress_batch call accepts
 
 struct ChunkDesc {
     uint32_t tensor;                     // index into the pointer tables
@@ -234,31 +235,16 @@ __device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, ui
     __syncthreads();
 }
 
-// Lines 1-4 of the update equations for one chunk per workgroup.
-template <int MODE, int QUANT>
-__global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __restrict__ chunks,
-                                                            const void* const* __restrict__ src_a,
-                                                            const void* const* __restrict__ src_b,
-                                                            float* const* __restrict__ ef_tab, float beta,
-                                                            uint32_t kappa, int force_radix,
-                                                            uint16_t* __restrict__ pairs_out,
-                                                            float* __restrict__ aux_out) {
-    __shared__ __align__(16) SelectShared sh;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint64_t c = blockIdx.x;
-    const ChunkDesc d = chunks[c];
-    const uint32_t n_c = d.n_c;
+// Top-kappa selection, quantiser, packing and residual for the chunk held in x[16] (already
+// folded).  On return x holds the new error-feedback values; the chunk's pairs, its levels (or
+// sent values) and its padding have been written.  All 256 lanes must call it; it ends with every
+// lane past its last read of `sh`, but callers that reuse `sh` must place a barrier first.
+template <int QUANT>
+__device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x)[16], int tid, int lane, int wave,
+                                                     uint32_t n_c, uint32_t kappa, int force_radix,
+                                                     uint16_t* __restrict__ pairs_c, float* __restrict__ values_c,
+                                                     float* __restrict__ scales_c) {
     const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
-    const void* pa = src_a[d.tensor];
-    const void* pb = MODE == MODE_PARAMS_F32 ? src_b[d.tensor] : nullptr;
-    float* pe = ef_tab[d.tensor];
-
-    float x[16];
-    if (n_c == (uint32_t)kChunk) load_fold_full<MODE>(pa, pb, pe, d.offset, tid, beta, x);
-    else load_fold_partial<MODE>(pa, pb, pe, d.offset, tid, beta, n_c, x);
-
     sh.cand[tid] = 0;
     if (tid < 2) sh.cand[kCandCap + tid] = 0;
     if (tid < 16) sh.bucket[tid] = 0;
@@ -362,8 +348,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
             run += sh.bucket[b];
         }
     }
-    uint16_t* pairs_c = pairs_out + c * kappa;
-    float* values_c = aux_out + c * kappa;          // identity mode only
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         bool sel[4];
@@ -404,13 +388,16 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
         if (QUANT == SPLC_QUANT_NONE) values_c[t] = 0.f;
     }
     if (QUANT == SPLC_QUANT_2BIT && tid == 0) {
-        aux_out[2 * c] = lo;
-        aux_out[2 * c + 1] = hi;
+        scales_c[0] = lo;
+        scales_c[1] = hi;
     }
+}
 
-    // ---- the error-feedback buffer is rewritten densely ----
+// The error-feedback buffer is rewritten densely (line 4 of the update equations).
+__device__ __forceinline__ void store_ef(float* __restrict__ pe, uint64_t off, int tid, uint32_t n_c,
+                                         const float (&x)[16]) {
     if (n_c == (uint32_t)kChunk) {
-        float4* po = reinterpret_cast<float4*>(pe + d.offset);
+        float4* po = reinterpret_cast<float4*>(pe + off);
 #pragma unroll
         for (int s = 0; s < 4; ++s)
             stream_store(po + s * kThreads + tid, make_float4(x[4 * s], x[4 * s + 1], x[4 * s + 2], x[4 * s + 3]));
@@ -418,8 +405,114 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
 #pragma unroll
         for (int el = 0; el < 16; ++el) {
             uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
-            if (idx < n_c) pe[d.offset + idx] = x[el];
+            if (idx < n_c) pe[off + idx] = x[el];
         }
+    }
+}
+
+// Lines 1-4 of the update equations, one replica, one chunk per workgroup.
+template <int MODE, int QUANT>
+__global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __restrict__ chunks,
+                                                            const void* const* __restrict__ src_a,
+                                                            const void* const* __restrict__ src_b,
+                                                            float* const* __restrict__ ef_tab, float beta,
+                                                            uint32_t kappa, int force_radix,
+                                                            uint16_t* __restrict__ pairs_out,
+                                                            float* __restrict__ aux_out) {
+    __shared__ __align__(16) SelectShared sh;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint64_t c = blockIdx.x;
+    const ChunkDesc d = chunks[c];
+    const uint32_t n_c = d.n_c;
+    const void* pa = src_a[d.tensor];
+    const void* pb = MODE == MODE_PARAMS_F32 ? src_b[d.tensor] : nullptr;
+    float* pe = ef_tab[d.tensor];
+
+    float x[16];
+    if (n_c == (uint32_t)kChunk) load_fold_full<MODE>(pa, pb, pe, d.offset, tid, beta, x);
+    else load_fold_partial<MODE>(pa, pb, pe, d.offset, tid, beta, n_c, x);
+    select_quantise_pack<QUANT>(sh, x, tid, lane, wave, n_c, kappa, force_radix, pairs_out + c * kappa,
+                                aux_out + c * kappa, aux_out + 2 * c);
+    store_ef(pe, d.offset, tid, n_c, x);
+}
+
+// Lines 1-4 for R replicas that share theta_outer (several replicas simulated on one GPU): the
+// workgroup reads its theta_outer chunk once and walks the replicas, so theta_outer costs 4 bytes
+// per parameter per launch instead of per replica.  Per replica the arithmetic, the selection and
+// the outputs are those of compress_kernel.
+// Table layout (device): theta_local[r][t] at tl_tab[r * n_tensors + t], likewise ef_tab; message
+// buffers pairs_tab[r], aux_tab[r].
+template <int QUANT>
+__global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDesc* __restrict__ chunks,
+                                                                  int n_replicas, uint32_t n_tensors,
+                                                                  const float* const* __restrict__ to_tab,
+                                                                  const float* const* __restrict__ tl_tab,
+                                                                  float* const* __restrict__ ef_tab, float beta,
+                                                                  uint32_t kappa, int force_radix,
+                                                                  uint16_t* const* __restrict__ pairs_tab,
+                                                                  float* const* __restrict__ aux_tab) {
+    __shared__ __align__(16) SelectShared sh;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint64_t c = blockIdx.x;
+    const ChunkDesc d = chunks[c];
+    const uint32_t n_c = d.n_c;
+    const bool full = n_c == (uint32_t)kChunk;
+    const float* po = to_tab[d.tensor] + d.offset;
+
+    // The theta_outer chunk waits in LDS (each lane re-reads only what it wrote, so no barrier is
+    // needed); keeping it in registers across the replica loop would cost occupancy.
+    __shared__ __align__(16) float so[kChunk];
+    float4* so4 = reinterpret_cast<float4*>(so);
+    if (full) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            so4[s * kThreads + tid] = stream_load(reinterpret_cast<const float4*>(po) + s * kThreads + tid);
+    } else {
+#pragma unroll
+        for (int el = 0; el < 16; ++el) {
+            uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+            so[idx] = idx < n_c ? po[idx] : 0.f;
+        }
+    }
+    for (int r = 0; r < n_replicas; ++r) {
+        // Per-lane index arithmetic is recomputed in every round: hoisting it out of the loop would
+        // pin some 60 registers across the whole selection and halve the occupancy.
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        const float* pl = tl_tab[(size_t)r * n_tensors + d.tensor] + d.offset;
+        float* pe = ef_tab[(size_t)r * n_tensors + d.tensor];
+        float x[16];
+        if (full) {
+            float4 lv[4], ev[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) lv[s] = stream_load(reinterpret_cast<const float4*>(pl) + s * kThreads + t);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                ev[s] = stream_load(reinterpret_cast<const float4*>(pe + d.offset) + s * kThreads + t);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float4 ov = so4[s * kThreads + t];
+                x[4 * s + 0] = fold(beta, ev[s].x, __fsub_rn(ov.x, lv[s].x));
+                x[4 * s + 1] = fold(beta, ev[s].y, __fsub_rn(ov.y, lv[s].y));
+                x[4 * s + 2] = fold(beta, ev[s].z, __fsub_rn(ov.z, lv[s].z));
+                x[4 * s + 3] = fold(beta, ev[s].w, __fsub_rn(ov.w, lv[s].w));
+            }
+        } else {
+#pragma unroll
+            for (int el = 0; el < 16; ++el) {
+                uint32_t idx = (el >> 2) * 1024 + t * 4 + (el & 3);
+                x[el] = idx < n_c ? fold(beta, pe[d.offset + idx], __fsub_rn(so[idx], pl[idx])) : 0.f;
+            }
+        }
+        float* aux_r = aux_tab[r];
+        select_quantise_pack<QUANT>(sh, x, t, t & 63, wave, n_c, kappa, force_radix, pairs_tab[r] + c * kappa,
+                                    aux_r + c * kappa, aux_r + 2 * c);
+        store_ef(pe, d.offset, t, n_c, x);
+        __syncthreads();          // every lane is done with `sh` before the next replica re-initialises it
     }
 }
 
@@ -701,7 +794,11 @@ int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* 
         }
     }
     int rc = SPLC_OK;
-    const size_t n_ptrs = 3 * (size_t)n_tensors + 2 * (size_t)kMaxReplicas;      // largest table of any call
+    // largest pointer table of any call: aggregate (2 per replica + 2 per tensor), compress (3 per
+    // tensor), compress_batch ((1 + 2 R) per tensor + 2 R)
+    size_t n_ptrs = 3 * (size_t)n_tensors + 2 * (size_t)kMaxReplicas;
+    const size_t n_batch = (1 + 2 * (size_t)kMaxBatch) * (size_t)n_tensors + 2 * (size_t)kMaxBatch;
+    if (n_batch > n_ptrs) n_ptrs = n_batch;
     plan->slot_bytes = (n_ptrs * sizeof(void*) + 255) & ~(size_t)255;
     if (n_chunks > 0 &&
         hipMalloc(reinterpret_cast<void**>(&plan->d_chunks), (size_t)n_chunks * sizeof(ChunkDesc)) != hipSuccess)
@@ -813,6 +910,65 @@ int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype, co
             else launch_compress<MODE_DIRECT_BF16, SPLC_QUANT_NONE>(plan, da, db, de, beta, pairs_out, aux_out, st);
             break;
     }
+    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
+    return slot_release(plan, slot, st);
+}
+
+int sparseloco_compress_batch(sparseloco_plan* plan, int n_replicas, const float* const* theta_outer,
+                              const float* const* const* theta_local, float* const* const* ef, float beta,
+                              uint16_t* const* pairs_out, float* const* aux_out, void* stream) {
+    if (!plan || !theta_outer || !theta_local || !ef || !pairs_out || !aux_out) return SPLC_EINVAL;
+    if (n_replicas < 1 || n_replicas > kMaxBatch) return SPLC_EINVAL;
+    if (!(beta == beta) || beta - beta != 0.f) return SPLC_EINVAL;
+    for (int r = 0; r < n_replicas; ++r) {
+        if (!theta_local[r] || !ef[r] || !pairs_out[r] || !aux_out[r]) return SPLC_EINVAL;
+        if (!aligned(pairs_out[r], 2) || !aligned(aux_out[r], 4)) return SPLC_EALIGN;
+    }
+    for (int i = 0; i < plan->n_tensors; ++i) {
+        if (plan->numel[i] == 0) continue;
+        if (!theta_outer[i]) return SPLC_EINVAL;
+        if (!aligned(theta_outer[i], 16)) return SPLC_EALIGN;
+        for (int r = 0; r < n_replicas; ++r) {
+            if (!theta_local[r][i] || !ef[r][i]) return SPLC_EINVAL;
+            if (!aligned(theta_local[r][i], 16) || !aligned(ef[r][i], 16)) return SPLC_EALIGN;
+        }
+    }
+    int rc = check_device(plan);
+    if (rc != SPLC_OK) return rc;
+    if (plan->n_chunks == 0) return SPLC_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int slot;
+    char* h;
+    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
+    const size_t nt = (size_t)plan->n_tensors, nr = (size_t)n_replicas;
+    void** tab = reinterpret_cast<void**>(h);
+    // [theta_outer: nt][theta_local: nr*nt][ef: nr*nt][pairs: nr][aux: nr]
+    for (size_t i = 0; i < nt; ++i) tab[i] = const_cast<float*>(theta_outer[i]);
+    for (size_t r = 0; r < nr; ++r) {
+        for (size_t i = 0; i < nt; ++i) {
+            tab[nt + r * nt + i] = const_cast<float*>(theta_local[r][i]);
+            tab[nt + nr * nt + r * nt + i] = ef[r][i];
+        }
+        tab[nt + 2 * nr * nt + r] = pairs_out[r];
+        tab[nt + 2 * nr * nt + nr + r] = aux_out[r];
+    }
+    char* dtab;
+    const size_t total = nt + 2 * nr * nt + 2 * nr;
+    if ((rc = slot_upload(plan, slot, total * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
+    const float* const* d_to = reinterpret_cast<const float* const*>(dtab);
+    const float* const* d_tl = reinterpret_cast<const float* const*>(dtab + nt * sizeof(void*));
+    float* const* d_ef = reinterpret_cast<float* const*>(dtab + (nt + nr * nt) * sizeof(void*));
+    uint16_t* const* d_pairs = reinterpret_cast<uint16_t* const*>(dtab + (nt + 2 * nr * nt) * sizeof(void*));
+    float* const* d_aux = reinterpret_cast<float* const*>(dtab + (nt + 2 * nr * nt + nr) * sizeof(void*));
+    const dim3 grid((unsigned)plan->n_chunks), block(kThreads);
+    const int force = plan->select == SPLC_SELECT_RADIX ? 1 : 0;
+    if (plan->quant == SPLC_QUANT_2BIT)
+        hipLaunchKernelGGL((compress_batch_kernel<SPLC_QUANT_2BIT>), grid, block, 0, st, plan->d_chunks, n_replicas,
+                           (uint32_t)nt, d_to, d_tl, d_ef, beta, (uint32_t)plan->kappa, force, d_pairs, d_aux);
+    else
+        hipLaunchKernelGGL((compress_batch_kernel<SPLC_QUANT_NONE>), grid, block, 0, st, plan->d_chunks, n_replicas,
+                           (uint32_t)nt, d_to, d_tl, d_ef, beta, (uint32_t)plan->kappa, force, d_pairs, d_aux);
     if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
     return slot_release(plan, slot, st);
 }

@@ -79,7 +79,7 @@ def _dev(x: np.ndarray, bf16: bool = False) -> torch.Tensor:
 
 
 def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AUTO, outer_steps=1,
-            deltas_per_step=None, stream: Optional[torch.cuda.Stream] = None, fused=None):
+            deltas_per_step=None, stream: Optional[torch.cuda.Stream] = None, fused=None, batch=False):
     """fused: None = aggregate then outer_update; "with_mean" / "no_mean" = sparseloco_aggregate_update
     with / without the dense mean output (without it, the returned mean is recomputed by a separate
     sparseloco_aggregate call, which the fused call must agree with anyway)."""
@@ -96,7 +96,9 @@ def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AU
             for p, a in msgs:                       # poison: the library must overwrite everything
                 p.fill_(0x5A5A)
                 a.fill_(float("nan"))
-            for r in range(case.R):
+            if batch:
+                B.sparseloco_compress_batch(plan, th, tl, ef, [m[0] for m in msgs], [m[1] for m in msgs], beta)
+            for r in range(case.R if not batch else 0):
                 p, a = msgs[r]
                 if case.delta is not None:
                     src = case.delta[r] if deltas_per_step is None else deltas_per_step[step][r]
@@ -141,8 +143,8 @@ def compare(got, want, what=""):
 
 
 def check(case: HostCase, kappa, beta=0.95, lr=1.0, quant=True, select=B.SPLC_SELECT_AUTO, outer_steps=1,
-          deltas_per_step=None, what="", fused=None):
+          deltas_per_step=None, what="", fused=None, batch=False):
     want = run_oracle(case, kappa, beta, lr, quant, outer_steps, deltas_per_step)
-    got = run_gpu(case, kappa, beta, lr, quant, select, outer_steps, deltas_per_step, fused=fused)
+    got = run_gpu(case, kappa, beta, lr, quant, select, outer_steps, deltas_per_step, fused=fused, batch=batch)
     compare(got, want, what)
     return got, want

@@ -84,6 +84,13 @@ def test_fused_aggregate_update(kappa, R, quant, fused):
     parity.check(case, kappa, lr=0.8, quant=quant, fused=fused, outer_steps=2, what="fused %s" % fused)
 
 
+@pytest.mark.parametrize("select", [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX])
+@pytest.mark.parametrize("kappa,R,quant", [(32, 1, True), (64, 8, True), (128, 5, False), (300, 3, True)])
+def test_batched_compress_matches_the_oracle(kappa, R, quant, select):
+    case = gaussian_case(RAGGED, R=R, seed=200 + kappa + R, heavy=True)
+    parity.check(case, kappa, quant=quant, select=select, batch=True, outer_steps=2, what="batched compress")
+
+
 def test_colliding_indices_many_replicas():
     """All replicas send (almost) the same indices: every accumulator entry gets R addends."""
     rng = np.random.default_rng(77)
