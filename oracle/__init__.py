@@ -44,13 +44,13 @@ def _load():
         c_f = ctypes.POINTER(ctypes.c_float)
         c_u16 = ctypes.POINTER(ctypes.c_uint16)
         lib.oracle_compress.restype = ctypes.c_int
-        lib.oracle_compress.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_int,
+        i64, ci = ctypes.c_int64, ctypes.c_int
+        lib.oracle_compress.argtypes = [i64, i64, ci, ci, ci, ctypes.c_float, ci,
                                         c_f, c_f, c_f, c_u16, c_f, c_u16, c_f, c_f]
         lib.oracle_decode.restype = ctypes.c_int
-        lib.oracle_decode.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                      c_u16, c_f, c_f, c_f]
+        lib.oracle_decode.argtypes = [i64, i64, ci, ci, ci, ci, c_u16, c_f, c_f, c_f]
         lib.oracle_aggregate.restype = ctypes.c_int
-        lib.oracle_aggregate.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        lib.oracle_aggregate.argtypes = [i64, i64, ci, ci, ci, ci, ci,
                                          ctypes.POINTER(c_u16), ctypes.POINTER(c_f), ctypes.POINTER(c_f), c_f]
         lib.oracle_outer_update.restype = ctypes.c_int
         lib.oracle_outer_update.argtypes = [ctypes.c_int64, c_f, c_f, ctypes.c_float]
@@ -72,17 +72,49 @@ def _u16p(a: Optional[np.ndarray]):
     return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))
 
 
-def num_chunks(numels: Sequence[int], chunk: int = 4096) -> int:
-    return sum((int(n) + chunk - 1) // chunk for n in numels)
+def _rc(shape) -> tuple:
+    """(rows, cols) of a tensor given its numel or its shape: 1-D -> (1, n); N-D -> (prod(leading), last)."""
+    if isinstance(shape, (int, np.integer)):
+        return 1, int(shape)
+    shape = tuple(int(v) for v in shape)
+    if len(shape) == 0:
+        return 1, 1
+    if len(shape) == 1:
+        return 1, shape[0]
+    rows = 1
+    for v in shape[:-1]:
+        rows *= v
+    return rows, shape[-1]
 
 
-def chunk_offsets(numels: Sequence[int], chunk: int = 4096) -> List[int]:
+def tensor_chunks(shape, chunk: int = 4096, tile: Optional[int] = None) -> int:
+    """Chunks of one tensor.  tile=None: flat chunks of `chunk` elements; tile=T: T x T blocks of the
+    (rows, cols) matrix (1-D tensors flat with chunk T*T)."""
+    rows, cols = _rc(shape)
+    if rows * cols == 0:
+        return 0
+    if tile is None or rows == 1:
+        ch = chunk if tile is None else tile * tile
+        return (rows * cols + ch - 1) // ch
+    return ((rows + tile - 1) // tile) * ((cols + tile - 1) // tile)
+
+
+def num_chunks(shapes: Sequence, chunk: int = 4096, tile: Optional[int] = None) -> int:
+    return sum(tensor_chunks(s, chunk, tile) for s in shapes)
+
+
+def chunk_offsets(shapes: Sequence, chunk: int = 4096, tile: Optional[int] = None) -> List[int]:
     """First chunk number of every tensor (chunks are numbered tensor by tensor)."""
     out, c = [], 0
-    for n in numels:
+    for s in shapes:
         out.append(c)
-        c += (int(n) + chunk - 1) // chunk
+        c += tensor_chunks(s, chunk, tile)
     return out
+
+
+def _geom(shape, chunk, tile):
+    rows, cols = _rc(shape)
+    return (rows, cols, tile, 1) if tile is not None else (1, rows * cols, chunk, 0)
 
 
 def set_threads(n: int) -> None:
@@ -95,8 +127,12 @@ def compress(ef: Sequence[np.ndarray], kappa: int, beta: float, *,
              theta_outer: Optional[Sequence[np.ndarray]] = None,
              theta_local: Optional[Sequence[np.ndarray]] = None,
              delta: Optional[Sequence[np.ndarray]] = None,
-             chunk: int = 4096, quant: bool = True):
+             chunk: int = 4096, quant: bool = True, shapes: Optional[Sequence] = None,
+             tile: Optional[int] = None):
     """One replica's compress over a list of tensors (flat views are taken).
+
+    Geometry: flat chunks of `chunk` elements, or, with tile=T and shapes (default: the arrays' own
+    shapes), T x T blocks of every tensor seen as a (rows, cols) matrix.
 
     ef: fp32 arrays, updated in place.  Either (theta_outer, theta_local) fp32,
     or delta: fp32 arrays, or uint16 arrays holding bfloat16 bit patterns.
@@ -105,15 +141,16 @@ def compress(ef: Sequence[np.ndarray], kappa: int, beta: float, *,
     """
     lib = _load()
     numels = [int(e.size) for e in ef]
-    nch = num_chunks(numels, chunk)
-    offs = chunk_offsets(numels, chunk)
+    shapes = [e.shape for e in ef] if shapes is None else list(shapes)
+    nch = num_chunks(shapes, chunk, tile)
+    offs = chunk_offsets(shapes, chunk, tile)
     pairs = np.empty(nch * kappa, np.uint16)
     scales = np.zeros(nch * 2, np.float32) if quant else None
     values = None if quant else np.zeros(nch * kappa, np.float32)
     for t, e in enumerate(ef):
         assert e.dtype == np.float32 and e.flags.c_contiguous
         c0 = offs[t]
-        tc = (numels[t] + chunk - 1) // chunk
+        tc = tensor_chunks(shapes[t], chunk, tile)
         p = pairs[c0 * kappa:(c0 + tc) * kappa]
         s = scales[c0 * 2:(c0 + tc) * 2] if quant else None
         v = None if quant else values[c0 * kappa:(c0 + tc) * kappa]
@@ -130,7 +167,7 @@ def compress(ef: Sequence[np.ndarray], kappa: int, beta: float, *,
             to = np.ascontiguousarray(theta_outer[t]).reshape(-1)
             tl = np.ascontiguousarray(theta_local[t]).reshape(-1)
             assert to.size == numels[t] and tl.size == numels[t]
-        rc = lib.oracle_compress(numels[t], chunk, kappa, beta, 1 if quant else 0,
+        rc = lib.oracle_compress(*_geom(shapes[t], chunk, tile), kappa, beta, 1 if quant else 0,
                                  _fp(to), _fp(tl), _fp(d32), _u16p(d16),
                                  _fp(e.reshape(-1)), _u16p(p), _fp(s), _fp(v))
         if rc != 0:
@@ -138,40 +175,45 @@ def compress(ef: Sequence[np.ndarray], kappa: int, beta: float, *,
     return (pairs, scales) if quant else (pairs, values)
 
 
-def decode(numels: Sequence[int], pairs: np.ndarray, aux: np.ndarray, kappa: int, *,
-           chunk: int = 4096, quant: bool = True) -> List[np.ndarray]:
-    """Dense fp32 arrays of one replica's message (zeros where nothing was sent)."""
+def decode(shapes: Sequence, pairs: np.ndarray, aux: np.ndarray, kappa: int, *,
+           chunk: int = 4096, quant: bool = True, tile: Optional[int] = None) -> List[np.ndarray]:
+    """Dense flat fp32 arrays of one replica's message (zeros where nothing was sent).
+    shapes: per tensor its numel or its shape."""
     lib = _load()
-    offs = chunk_offsets(numels, chunk)
+    offs = chunk_offsets(shapes, chunk, tile)
     out = []
-    for t, n in enumerate(numels):
-        n = int(n)
+    for t, shp in enumerate(shapes):
+        rows, cols = _rc(shp)
+        n = rows * cols
         c0 = offs[t]
-        tc = (n + chunk - 1) // chunk
+        tc = tensor_chunks(shp, chunk, tile)
         dense = np.empty(n, np.float32)
         p = pairs[c0 * kappa:(c0 + tc) * kappa]
         s = aux[c0 * 2:(c0 + tc) * 2] if quant else None
         v = None if quant else aux[c0 * kappa:(c0 + tc) * kappa]
-        rc = lib.oracle_decode(n, chunk, kappa, 1 if quant else 0, _u16p(p), _fp(s), _fp(v), _fp(dense))
+        rc = lib.oracle_decode(*_geom(shp, chunk, tile), kappa, 1 if quant else 0, _u16p(p), _fp(s), _fp(v),
+                               _fp(dense))
         if rc != 0:
             raise ValueError("oracle_decode failed: %d" % rc)
         out.append(dense)
     return out
 
 
-def aggregate(numels: Sequence[int], pairs: Sequence[np.ndarray], aux: Sequence[np.ndarray], kappa: int, *,
-              chunk: int = 4096, quant: bool = True) -> List[np.ndarray]:
-    """Mean over replicas of the decoded messages; returns dense fp32 arrays per tensor."""
+def aggregate(shapes: Sequence, pairs: Sequence[np.ndarray], aux: Sequence[np.ndarray], kappa: int, *,
+              chunk: int = 4096, quant: bool = True, tile: Optional[int] = None) -> List[np.ndarray]:
+    """Mean over replicas of the decoded messages; returns dense flat fp32 arrays per tensor.
+    shapes: per tensor its numel or its shape."""
     lib = _load()
     R = len(pairs)
-    offs = chunk_offsets(numels, chunk)
+    offs = chunk_offsets(shapes, chunk, tile)
     c_f = ctypes.POINTER(ctypes.c_float)
     c_u16 = ctypes.POINTER(ctypes.c_uint16)
     out = []
-    for t, n in enumerate(numels):
-        n = int(n)
+    for t, shp in enumerate(shapes):
+        rows, cols = _rc(shp)
+        n = rows * cols
         c0 = offs[t]
-        tc = (n + chunk - 1) // chunk
+        tc = tensor_chunks(shp, chunk, tile)
         ps = [pairs[r][c0 * kappa:(c0 + tc) * kappa] for r in range(R)]
         if quant:
             ss = [aux[r][c0 * 2:(c0 + tc) * 2] for r in range(R)]
@@ -183,7 +225,7 @@ def aggregate(numels: Sequence[int], pairs: Sequence[np.ndarray], aux: Sequence[
         sp = (c_f * R)(*[_fp(s) for s in ss]) if ss is not None else None
         vp = (c_f * R)(*[_fp(v) for v in vs]) if vs is not None else None
         dense = np.empty(n, np.float32)
-        rc = lib.oracle_aggregate(n, chunk, kappa, 1 if quant else 0, R, pp, sp, vp, _fp(dense))
+        rc = lib.oracle_aggregate(*_geom(shp, chunk, tile), kappa, 1 if quant else 0, R, pp, sp, vp, _fp(dense))
         if rc != 0:
             raise ValueError("oracle_aggregate failed: %d" % rc)
         out.append(dense)
