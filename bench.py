@@ -46,7 +46,7 @@ def read_traffic(workload_name):
         return None
 
 
-def cpu_baseline(rs, cfg, sample_tensors, quant=True):
+def cpu_baseline(rs, cfg, sample_tensors, quant=True, shapes=None):
     """The oracle, as it stands, on the host cores: one full outer step (R x compress +
     aggregate + update) over a fixed tensor subset of the same workload."""
     import numpy as np
@@ -65,18 +65,20 @@ def cpu_baseline(rs, cfg, sample_tensors, quant=True):
         src = [[to_np(rs.delta[r][i]) for i in sample_tensors] for r in range(rs.R)]
     else:
         src = [[to_np(rs.theta_local[r][i]) for i in sample_tensors] for r in range(rs.R)]
+    geo = dict(shapes=shapes, tile=64) if shapes is not None else {}
     threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
     oracle.set_threads(threads)
     t0 = time.perf_counter()
     pairs, aux = [], []
     for r in range(rs.R):
         if rs.direct:
-            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], delta=src[r], quant=quant)
+            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], delta=src[r], quant=quant, **geo)
         else:
             p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], theta_outer=th, theta_local=src[r],
-                                   quant=quant)
+                                   quant=quant, **geo)
         pairs.append(p), aux.append(a)
-    dbar = oracle.aggregate(numels, pairs, aux, cfg["kappa"], quant=quant)
+    dbar = oracle.aggregate(shapes if shapes is not None else numels, pairs, aux, cfg["kappa"], quant=quant,
+                            tile=64 if shapes is not None else None)
     oracle.outer_update(th, dbar, cfg["outer_lr"])
     dt = time.perf_counter() - t0
     n = sum(numels)
@@ -95,6 +97,8 @@ def main():
     ap.add_argument("--replicas", type=int, default=None)
     ap.add_argument("--quant", choices=["2bit", "none"], default="2bit",
                     help="2bit: sign + one magnitude bit (default); none: Q = identity, fp32 values in the message")
+    ap.add_argument("--layout", choices=["flat", "tile"], default="flat",
+                    help="flat: chunks of 4096 consecutive elements (default); tile: 64 x 64 tiles of each matrix")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for rocprofv3 --pmc byte counters)")
@@ -124,7 +128,9 @@ def main():
              torch.cuda.memory_allocated() / 1e9), file=sys.stderr, flush=True)
 
     quant = args.quant == "2bit"
-    plan = B.Plan(rs.numels, cfg["kappa"], quant)
+    tiled = args.layout == "tile"
+    shapes = [W.tensor_shapes(args.workload)[t] for t in rs.tensor_ids]
+    plan = B.Plan(shapes if tiled else rs.numels, cfg["kappa"], quant, tiled=tiled)
     msgs = [plan.message_buffers() for _ in range(R)]
     dbar = [torch.empty(n, device="cuda") for n in rs.numels]
     t_theta = B.ptr_table(rs.theta_outer)
@@ -253,9 +259,10 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "%s: %d tensors, %d params, kappa=%d per 4096-chunk, R=%d replicas, beta=%g, "
-                               "%s, outer_lr=%g" % (cfg["name"], len(rs.numels), n, cfg["kappa"], R, cfg["beta"],
-                                                     "2-bit quantiser" if quant else "Q = identity (fp32 values)",
-                                                     cfg["outer_lr"]),
+                               "%s, outer_lr=%g, %s" % (cfg["name"], len(rs.numels), n, cfg["kappa"], R, cfg["beta"],
+                                                         "2-bit quantiser" if quant else "Q = identity (fp32 values)",
+                                                         cfg["outer_lr"],
+                                                         "64x64 tile chunks" if tiled else "flat 4096-element chunks"),
                    "n_params": n, "n_chunks": nch, "kappa": cfg["kappa"], "replicas": R,
                    "step_algorithmic_bytes": total_bytes,
                    "step_frac_of_hbm_peak": gbs(total_bytes, ms_step) / HBM_PEAK_GBS,
@@ -270,7 +277,7 @@ def main():
     }
     if not args.no_cpu:
         sample = [i for i in range(min(54, len(rs.numels)))]
-        result["cpu_baseline"] = cpu_baseline(rs, cfg, sample, quant)
+        result["cpu_baseline"] = cpu_baseline(rs, cfg, sample, quant, [shapes[i] for i in sample] if tiled else None)
     plan.close()
     print(json.dumps(result), flush=True)
 

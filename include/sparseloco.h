@@ -28,10 +28,11 @@
  *   - fp32 arithmetic is IEEE-754 round-to-nearest, one rounding per operation
  *     (no fused multiply-add), denormals kept.  Inputs must be finite.
  *   - A tensor is its row-major flattening; chunk = SPLC_CHUNK consecutive
- *     elements; the last chunk of a tensor may be shorter and keeps
+ *     elements (sparseloco_plan_create) or a 64 x 64 tile
+ *     (sparseloco_plan_create_2d); an edge chunk with n_c elements keeps
  *     min(kappa, n_c) entries.  Chunks are numbered tensor by tensor in the
- *     order given to sparseloco_plan_create.  Magnitude ties go to the lower
- *     index.
+ *     order given at plan creation.  Magnitude ties go to the lower index.
+ *   - Tensor pointers need 4-byte alignment only.
  *
  * Message layout (per replica)
  *   pairs  uint16[n_chunks * kappa]   pairs[c*kappa + t] = index | code << 12,
@@ -58,7 +59,7 @@ extern "C" {
 enum {
     SPLC_OK = 0,
     SPLC_EINVAL = -1,            /* bad argument (NULL, size, range, mode) */
-    SPLC_EALIGN = -2,            /* a tensor pointer is not 16-byte aligned (8-byte for bf16 sources) */
+    SPLC_EALIGN = -2,            /* a tensor pointer is not 4-byte aligned */
     SPLC_ENOMEM = -3,            /* host or device allocation failed */
     SPLC_EHIP = -4,              /* a HIP runtime call failed */
     SPLC_EPLAN = -5              /* call does not match the plan (quantiser mode, device) */
@@ -74,6 +75,11 @@ enum {
 enum {
     SPLC_QUANT_NONE = 0,         /* Q = identity: the setting of the paper's experiments */
     SPLC_QUANT_2BIT = 1          /* sign + one magnitude bit, two levels per chunk */
+};
+
+enum {
+    SPLC_LAYOUT_FLAT = 0,        /* chunk = 4096 consecutive elements of the flattened tensor */
+    SPLC_LAYOUT_TILE64 = 1       /* chunk = 64 x 64 tile of the tensor seen as a matrix */
 };
 
 enum {
@@ -93,12 +99,25 @@ typedef struct sparseloco_plan sparseloco_plan;
  */
 int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel,
                            int kappa, int quant_mode);
+/*
+ * The same with the chunk read literally as a 64 x 64 tile (section 3: "a chunk
+ * size of 64 x 64 (i.e., 4096 elements per chunk)").  Tensor i is a row-major
+ * rows[i] x cols[i] matrix (fold leading dimensions into rows); tile (bi, bj)
+ * covers rows 64*bi.. and columns 64*bj.., tiles are numbered row-major and edge
+ * tiles are smaller (h x w elements, kappa_c = min(kappa, h*w)).  Inside a tile
+ * the element at local row lr, local column lc has index lr*64 + lc, so pairs
+ * keep their 12-bit index.  Tensors with rows[i] == 1 are chunked flat.
+ * cols[i] < 2^24.
+ */
+int sparseloco_plan_create_2d(sparseloco_plan** out, int n_tensors, const int64_t* rows,
+                              const int64_t* cols, int kappa, int quant_mode);
 void sparseloco_plan_destroy(sparseloco_plan* plan);
 
 int64_t sparseloco_plan_num_chunks(const sparseloco_plan* plan);   /* sum over tensors of ceil(numel / SPLC_CHUNK) */
 int64_t sparseloco_plan_num_params(const sparseloco_plan* plan);   /* sum of numel */
 int sparseloco_plan_kappa(const sparseloco_plan* plan);
 int sparseloco_plan_quant_mode(const sparseloco_plan* plan);
+int sparseloco_plan_layout(const sparseloco_plan* plan);            /* SPLC_LAYOUT_* */
 /* SPLC_SELECT_*: which selection algorithm the compress kernel uses. */
 int sparseloco_plan_set_select(sparseloco_plan* plan, int select_mode);
 

@@ -22,9 +22,11 @@ SPLC_F32, SPLC_BF16 = 0, 1
 SPLC_DELTA_FROM_PARAMS, SPLC_DELTA_DIRECT = 0, 1
 SPLC_QUANT_NONE, SPLC_QUANT_2BIT = 0, 1
 SPLC_SELECT_AUTO, SPLC_SELECT_RADIX = 0, 1
+SPLC_LAYOUT_FLAT, SPLC_LAYOUT_TILE64 = 0, 1
 
 EXPORTS = [
-    "sparseloco_plan_create", "sparseloco_plan_destroy", "sparseloco_plan_num_chunks",
+    "sparseloco_plan_create", "sparseloco_plan_create_2d", "sparseloco_plan_destroy", "sparseloco_plan_num_chunks",
+    "sparseloco_plan_layout",
     "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
     "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
     "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
@@ -51,6 +53,10 @@ def lib():
         pp = ctypes.POINTER(ctypes.c_void_p)
         L.sparseloco_plan_create.restype = i32
         L.sparseloco_plan_create.argtypes = [pp, i32, ctypes.POINTER(i64), i32, i32]
+        L.sparseloco_plan_create_2d.restype = i32
+        L.sparseloco_plan_create_2d.argtypes = [pp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64), i32, i32]
+        L.sparseloco_plan_layout.restype = i32
+        L.sparseloco_plan_layout.argtypes = [vp]
         L.sparseloco_plan_destroy.restype = None
         L.sparseloco_plan_destroy.argtypes = [vp]
         L.sparseloco_plan_num_chunks.restype = i64
@@ -98,19 +104,44 @@ def _stream(stream) -> Optional[int]:
     return h or None
 
 
-class Plan:
-    """Chunk table and staging slots for a list of tensor sizes (sparseloco_plan_create)."""
+def rows_cols(shape):
+    """(rows, cols) of a tensor for the tiled layout: leading dimensions fold into rows; 1-D -> (1, n)."""
+    if isinstance(shape, int):
+        return 1, int(shape)
+    shape = tuple(int(v) for v in shape)
+    if len(shape) <= 1:
+        return 1, (shape[0] if shape else 1)
+    rows = 1
+    for v in shape[:-1]:
+        rows *= v
+    return rows, shape[-1]
 
-    def __init__(self, numels: Sequence[int], kappa: int, quant: bool = True):
+
+class Plan:
+    """Chunk table and staging slots for a list of tensors.
+
+    shapes: per tensor its numel (int) or its shape.  tiled=False: chunks are 4096 consecutive
+    elements (sparseloco_plan_create); tiled=True: 64 x 64 tiles of each tensor seen as a
+    (rows, cols) matrix (sparseloco_plan_create_2d)."""
+
+    def __init__(self, shapes: Sequence, kappa: int, quant: bool = True, tiled: bool = False):
         self._h = ctypes.c_void_p()
-        n = len(numels)
-        arr = (ctypes.c_int64 * max(n, 1))(*[int(v) for v in numels])
-        rc = lib().sparseloco_plan_create(ctypes.byref(self._h), n, arr, int(kappa),
-                                          SPLC_QUANT_2BIT if quant else SPLC_QUANT_NONE)
+        n = len(shapes)
+        rc_list = [rows_cols(s) for s in shapes]
+        numels = [r * c for r, c in rc_list]
+        q = SPLC_QUANT_2BIT if quant else SPLC_QUANT_NONE
+        if tiled:
+            rows = (ctypes.c_int64 * max(n, 1))(*[r for r, _ in rc_list])
+            cols = (ctypes.c_int64 * max(n, 1))(*[c for _, c in rc_list])
+            rc = lib().sparseloco_plan_create_2d(ctypes.byref(self._h), n, rows, cols, int(kappa), q)
+        else:
+            arr = (ctypes.c_int64 * max(n, 1))(*numels)
+            rc = lib().sparseloco_plan_create(ctypes.byref(self._h), n, arr, int(kappa), q)
         if rc != SPLC_OK:
             self._h = ctypes.c_void_p()
             raise SparseLoCoError(rc, "sparseloco_plan_create")
-        self.numels = [int(v) for v in numels]
+        self.numels = numels
+        self.tiled = bool(tiled)
         self.kappa = int(kappa)
         self.quant = bool(quant)
 

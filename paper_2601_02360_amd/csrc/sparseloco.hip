@@ -8,13 +8,19 @@
 // only for the small hand-offs of the selection.
 //
 // Element layout of a chunk inside a workgroup: lane `tid` holds, for slot
-// s = 0..3 and j = 0..3, element index  s*1024 + tid*4 + j  (one float4 per
-// slot), so every load instruction of the workgroup covers 4 KiB contiguous.
+// s = 0..3 and j = 0..3, local index  s*1024 + tid*4 + j  (one float4 per slot).
+// A chunk is addressed as 64 local rows of 64 elements: local index idx sits at
+// element  offset + (idx >> 6) * stride + (idx & 63)  of its tensor.  A flat chunk
+// has stride 64 (every load instruction of the workgroup then covers 4 KiB
+// contiguous); a 64 x 64 tile of a matrix has stride = number of columns (256-byte
+// row segments).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "sparseloco.h"
@@ -31,29 +37,72 @@ constexpr int kMaxBatch = 64;              // replicas one compress_batch call a
 
 struct ChunkDesc {
     uint32_t tensor;                     // index into the pointer tables
-    uint32_t n_c;                        // elements in this chunk (kChunk except a tensor's last)
-    uint64_t offset;                     // element offset of the chunk inside its tensor
+    uint32_t n_c;                        // elements in this chunk (kChunk unless it is an edge chunk)
+    uint64_t offset;                     // element offset of local index 0 inside its tensor
+    uint32_t stride;                     // elements between local rows: 64 (flat) or the matrix's columns (tile)
+    uint8_t h;                           // local rows present (1..64)
+    uint8_t w;                           // width of every row but the last
+    uint8_t last_w;                      // width of the last row (flat tail), = w for a tile
+    uint8_t vec;                         // 4-element vector accesses apply: bit 0 for fp32 arrays (all 4096
+                                         // elements present), bit 1 for bf16 arrays (also every row start even)
+    uint32_t id;                         // chunk number (position of its message in pairs / scales / values)
+    uint32_t reserved;
 };
+static_assert(sizeof(ChunkDesc) == 32, "chunk table entries are 32 bytes");
+
+// Local index -> present in the chunk?
+__device__ __forceinline__ bool present(const ChunkDesc& d, uint32_t idx) {
+    const uint32_t lr = idx >> 6, lc = idx & 63u;
+    return lr + 1 < d.h ? lc < d.w : (lr + 1 == d.h && lc < d.last_w);
+}
+// Local index -> element offset from the chunk's origin.
+__device__ __forceinline__ uint32_t elem_of(const ChunkDesc& d, uint32_t idx) {
+    return (idx >> 6) * d.stride + (idx & 63u);
+}
+// Address of lane tid's 4-element vector in slot s (local rows 16 s + tid / 16, columns 4 (tid % 16)...).
+// The slot part is uniform and stays in scalar registers; the per-lane part is one 32-bit byte
+// offset shared by all slots and arrays (a chunk spans less than 4 GiB: stride < 2^24).
+template <class T>
+__device__ __forceinline__ T* vec_at(T* origin, const ChunkDesc& d, int tid, int s) {
+    const uint32_t lane_bytes = ((uint32_t)(tid >> 4) * d.stride + (uint32_t)(tid & 15) * 4u) * (uint32_t)sizeof(T);
+    const uint64_t slot_bytes = (uint64_t)((uint32_t)s * 16u * d.stride) * sizeof(T);
+    using Byte = typename std::conditional<std::is_const<T>::value, const char, char>::type;
+    return reinterpret_cast<T*>(reinterpret_cast<Byte*>(origin) + slot_bytes + lane_bytes);
+}
+// Bit el of the result: element el of lane tid is present.
+__device__ __forceinline__ uint32_t present_mask(const ChunkDesc& d, int tid) {
+    if (d.n_c == (uint32_t)kChunk) return 0xFFFFu;
+    uint32_t m = 0;
+#pragma unroll
+    for (int el = 0; el < 16; ++el)
+        m |= present(d, (uint32_t)((el >> 2) * 1024 + tid * 4 + (el & 3))) ? (1u << el) : 0u;
+    return m;
+}
 
 enum { MODE_PARAMS_F32 = 0, MODE_DIRECT_F32 = 1, MODE_DIRECT_BF16 = 2 };
 
 // Streaming accesses: every dense array is touched exactly once per launch, so loads and stores
 // carry the non-temporal hint (measured on MI355X: 3 reads + 1 write streams at ~6.0 TB/s with
 // the hint against ~5.6 TB/s without).
-typedef float vfloat4 __attribute__((ext_vector_type(4)));
-typedef uint32_t vuint2 __attribute__((ext_vector_type(2)));
+// The vector types promise only 4-byte alignment: rows of a tile start at any multiple of 4 bytes,
+// and global memory accepts dword-aligned multi-dword accesses.
+typedef float vfloat4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t vuint2 __attribute__((ext_vector_type(2), aligned(4)));
 
-__device__ __forceinline__ float4 stream_load(const float4* p) {
-    vfloat4 v = __builtin_nontemporal_load(reinterpret_cast<const vfloat4*>(p));
+// Every tensor lives in global memory; saying so lets the compiler emit global_ instead of flat_
+// instructions.
+#define SPLC_GLOBAL __attribute__((address_space(1)))
+__device__ __forceinline__ float4 stream_load4(const float* p) {
+    vfloat4 v = __builtin_nontemporal_load((const SPLC_GLOBAL vfloat4*)p);
     return make_float4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ uint2 stream_load(const uint2* p) {
-    vuint2 v = __builtin_nontemporal_load(reinterpret_cast<const vuint2*>(p));
+__device__ __forceinline__ uint2 stream_load4(const uint16_t* p) {       // four bf16
+    vuint2 v = __builtin_nontemporal_load((const SPLC_GLOBAL vuint2*)p);
     return make_uint2(v.x, v.y);
 }
-__device__ __forceinline__ void stream_store(float4* p, float4 v) {
+__device__ __forceinline__ void stream_store4(float* p, float4 v) {
     vfloat4 t = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(t, reinterpret_cast<vfloat4*>(p));
+    __builtin_nontemporal_store(t, (SPLC_GLOBAL vfloat4*)p);
 }
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
@@ -76,20 +125,20 @@ __device__ __forceinline__ float fold(float beta, float e, float delta) {
 
 template <int MODE>
 __device__ __forceinline__ void load_fold_full(const void* __restrict__ a, const void* __restrict__ b,
-                                               const float* __restrict__ e, uint64_t off, int tid, float beta,
-                                               float (&x)[16]) {
-    const float4* pe = reinterpret_cast<const float4*>(e + off);
+                                               const float* __restrict__ e, const ChunkDesc& d, int tid,
+                                               float beta, float (&x)[16]) {
+    const float* pe = e + d.offset;
     float4 ev[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) ev[s] = stream_load(pe + s * kThreads + tid);
+    for (int s = 0; s < 4; ++s) ev[s] = stream_load4(vec_at(pe, d, tid, s));
     if (MODE == MODE_PARAMS_F32) {
-        const float4* po = reinterpret_cast<const float4*>(static_cast<const float*>(a) + off);
-        const float4* pl = reinterpret_cast<const float4*>(static_cast<const float*>(b) + off);
+        const float* po = static_cast<const float*>(a) + d.offset;
+        const float* pl = static_cast<const float*>(b) + d.offset;
         float4 ov[4], lv[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) ov[s] = stream_load(po + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) ov[s] = stream_load4(vec_at(po, d, tid, s));
 #pragma unroll
-        for (int s = 0; s < 4; ++s) lv[s] = stream_load(pl + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) lv[s] = stream_load4(vec_at(pl, d, tid, s));
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             x[4 * s + 0] = fold(beta, ev[s].x, __fsub_rn(ov[s].x, lv[s].x));
@@ -98,10 +147,10 @@ __device__ __forceinline__ void load_fold_full(const void* __restrict__ a, const
             x[4 * s + 3] = fold(beta, ev[s].w, __fsub_rn(ov[s].w, lv[s].w));
         }
     } else if (MODE == MODE_DIRECT_F32) {
-        const float4* pd = reinterpret_cast<const float4*>(static_cast<const float*>(a) + off);
+        const float* pd = static_cast<const float*>(a) + d.offset;
         float4 dv[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) dv[s] = stream_load(pd + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) dv[s] = stream_load4(vec_at(pd, d, tid, s));
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             x[4 * s + 0] = fold(beta, ev[s].x, dv[s].x);
@@ -111,10 +160,10 @@ __device__ __forceinline__ void load_fold_full(const void* __restrict__ a, const
         }
     } else {
         // bf16 -> fp32 is the exact widening: the 16 bits become the upper half of the word
-        const uint2* pd = reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a) + off);
+        const uint16_t* pd = static_cast<const uint16_t*>(a) + d.offset;
         uint2 dv[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) dv[s] = stream_load(pd + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) dv[s] = stream_load4(vec_at(pd, d, tid, s));
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             x[4 * s + 0] = fold(beta, ev[s].x, __uint_as_float(dv[s].x << 16));
@@ -125,29 +174,27 @@ __device__ __forceinline__ void load_fold_full(const void* __restrict__ a, const
     }
 }
 
+// Edge chunks and rows that do not allow vector accesses: element by element, absent elements = +0.
 template <int MODE>
-__device__ __forceinline__ void load_fold_partial(const void* __restrict__ a, const void* __restrict__ b,
-                                                  const float* __restrict__ e, uint64_t off, int tid, float beta,
-                                                  uint32_t n_c, float (&x)[16]) {
+__device__ __forceinline__ void load_fold_scalar(const void* __restrict__ a, const void* __restrict__ b,
+                                                 const float* __restrict__ e, const ChunkDesc& d, int tid,
+                                                 float beta, uint32_t pmask, float (&x)[16]) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t idx = s * 1024 + tid * 4 + j;
-            float v = 0.f;
-            if (idx < n_c) {
-                float ev = e[off + idx];
-                float d;
-                if (MODE == MODE_PARAMS_F32)
-                    d = __fsub_rn(static_cast<const float*>(a)[off + idx], static_cast<const float*>(b)[off + idx]);
-                else if (MODE == MODE_DIRECT_F32)
-                    d = static_cast<const float*>(a)[off + idx];
-                else
-                    d = __uint_as_float((uint32_t) static_cast<const uint16_t*>(a)[off + idx] << 16);
-                v = fold(beta, ev, d);
-            }
-            x[4 * s + j] = v;
+    for (int el = 0; el < 16; ++el) {
+        const uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+        float v = 0.f;
+        if (pmask & (1u << el)) {
+            const uint64_t at = d.offset + elem_of(d, idx);
+            float dl;
+            if (MODE == MODE_PARAMS_F32)
+                dl = __fsub_rn(static_cast<const float*>(a)[at], static_cast<const float*>(b)[at]);
+            else if (MODE == MODE_DIRECT_F32)
+                dl = static_cast<const float*>(a)[at];
+            else
+                dl = __uint_as_float((uint32_t) static_cast<const uint16_t*>(a)[at] << 16);
+            v = fold(beta, e[at], dl);
         }
+        x[el] = v;
     }
 }
 
@@ -166,9 +213,10 @@ struct SelectShared {
 
 // Exact kappa_c-th largest composite by most-significant-digit radix select over
 // the 43-bit composites (31 key bits, 12 inverted index bits).  Composites of
-// valid elements are distinct, so the result identifies one element: the last
-// one kept.  Works for any n_c <= 4096, any kappa_c in 1..n_c, any tie pattern.
-__device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, uint32_t n_c, uint32_t kappa_c) {
+// present elements are distinct, so the result identifies one element: the last
+// one kept.  Works for any set of present elements (bit el of pmask = element el of this lane is
+// present), any kappa_c in 1..n_c, any tie pattern.
+__device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, uint32_t pmask, uint32_t kappa_c) {
     const int lane = tid & 63;
     const int wave = tid >> 6;
     uint64_t prefix = 0;
@@ -183,8 +231,12 @@ __device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, ui
 #pragma unroll
         for (int el = 0; el < 16; ++el) {
             uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
-            uint64_t comp = ((uint64_t)(__float_as_uint(x[el]) & 0x7FFFFFFFu) << 12) | (uint64_t)(4095u - idx);
-            if (idx < n_c && (comp >> hi_bit) == prefix)
+            // The composite is rebuilt in every pass: kept across the passes, the sixteen 64-bit values
+            // of this rarely taken path would set the register count of the whole kernel.
+            uint32_t bits = __float_as_uint(x[el]);
+            asm volatile("" : "+v"(bits));
+            uint64_t comp = ((uint64_t)(bits & 0x7FFFFFFFu) << 12) | (uint64_t)(4095u - idx);
+            if ((pmask & (1u << el)) && (comp >> hi_bit) == prefix)
                 atomicAdd(&sh.hist[(uint32_t)(comp >> shift) & ((1u << width) - 1u)], 1u);
         }
         __syncthreads();
@@ -224,7 +276,7 @@ __device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, ui
         uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
         uint32_t key = __float_as_uint(x[el]) & 0x7FFFFFFFu;
         uint64_t comp = ((uint64_t)key << 12) | (uint64_t)(4095u - idx);
-        if (idx < n_c) {
+        if (pmask & (1u << el)) {
             tmax = key > tmax ? key : tmax;
             if (comp >= prefix) atomicAdd(&sh.bucket[idx >> 8], 1u);
         }
@@ -241,7 +293,7 @@ __device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, ui
 // lane past its last read of `sh`, but callers that reuse `sh` must place a barrier first.
 template <int QUANT>
 __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x)[16], int tid, int lane, int wave,
-                                                     uint32_t n_c, uint32_t kappa, int force_radix,
+                                                     uint32_t n_c, uint32_t pmask, uint32_t kappa, int force_radix,
                                                      uint16_t* __restrict__ pairs_c, float* __restrict__ values_c,
                                                      float* __restrict__ scales_c) {
     const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
@@ -321,7 +373,7 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
         }
     }
     __syncthreads();
-    if (!selected_by_filter) radix_select(sh, x, tid, n_c, kappa_c);
+    if (!selected_by_filter) radix_select(sh, x, tid, pmask, kappa_c);
 
     // ---- final pass: selection predicate, output positions, quantise, pack, residual ----
     const uint64_t thr = sh.thr;
@@ -356,7 +408,7 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
         for (int j = 0; j < 4; ++j) {
             uint32_t idx = s * 1024 + tid * 4 + j;
             uint32_t key = __float_as_uint(x[4 * s + j]) & 0x7FFFFFFFu;
-            sel[j] = idx < n_c && (key > T || (key == T && idx <= idxT));
+            sel[j] = (pmask & (1u << (4 * s + j))) && (key > T || (key == T && idx <= idxT));
             m4[j] = __ballot(sel[j]);
         }
         if ((m4[0] | m4[1] | m4[2] | m4[3]) != 0) {
@@ -394,25 +446,56 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
 }
 
 // The error-feedback buffer is rewritten densely (line 4 of the update equations).
-__device__ __forceinline__ void store_ef(float* __restrict__ pe, uint64_t off, int tid, uint32_t n_c,
+template <bool VEC>
+__device__ __forceinline__ void store_ef(float* __restrict__ e, const ChunkDesc& d, int tid, uint32_t pmask,
                                          const float (&x)[16]) {
-    if (n_c == (uint32_t)kChunk) {
-        float4* po = reinterpret_cast<float4*>(pe + off);
+    float* pe = e + d.offset;
+    if (VEC) {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-            stream_store(po + s * kThreads + tid, make_float4(x[4 * s], x[4 * s + 1], x[4 * s + 2], x[4 * s + 3]));
+            stream_store4(vec_at(pe, d, tid, s), make_float4(x[4 * s], x[4 * s + 1], x[4 * s + 2], x[4 * s + 3]));
     } else {
 #pragma unroll
         for (int el = 0; el < 16; ++el) {
-            uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
-            if (idx < n_c) pe[off + idx] = x[el];
+            const uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+            if (pmask & (1u << el)) pe[elem_of(d, idx)] = x[el];
         }
     }
 }
 
 // Lines 1-4 of the update equations, one replica, one chunk per workgroup.
+// VEC = true: the chunk is complete and allows 4-element vector accesses (the streaming path);
+// VEC = false: edge chunks and rows that start at odd bf16 elements, element by element.
+template <int MODE, int QUANT, bool VEC>
+__device__ __forceinline__ void compress_body(SelectShared& sh, const ChunkDesc* __restrict__ chunks,
+                                              const void* const* __restrict__ src_a,
+                                              const void* const* __restrict__ src_b,
+                                              float* const* __restrict__ ef_tab, float beta, uint32_t kappa,
+                                              int force_radix, uint16_t* __restrict__ pairs_out,
+                                              float* __restrict__ aux_out) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const ChunkDesc d = chunks[blockIdx.x];
+    const uint64_t c = d.id;
+    const void* pa = src_a[d.tensor];
+    const void* pb = MODE == MODE_PARAMS_F32 ? src_b[d.tensor] : nullptr;
+    float* pe = ef_tab[d.tensor];
+
+    const uint32_t pmask = VEC ? 0xFFFFu : present_mask(d, tid);
+    const uint32_t n_c = VEC ? (uint32_t)kChunk : d.n_c;
+    float x[16];
+    if (VEC) load_fold_full<MODE>(pa, pb, pe, d, tid, beta, x);
+    else load_fold_scalar<MODE>(pa, pb, pe, d, tid, beta, pmask, x);
+    select_quantise_pack<QUANT>(sh, x, tid, lane, wave, n_c, pmask, kappa, force_radix, pairs_out + c * kappa,
+                                aux_out + c * kappa, aux_out + 2 * c);
+    store_ef<VEC>(pe, d, tid, pmask, x);
+}
+
+// The chunk table lists the n_gen element-wise chunks first: workgroups from n_gen on take the
+// streaming path (one launch; the branch is uniform per workgroup).
 template <int MODE, int QUANT>
-__global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __restrict__ chunks,
+__global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n_gen,
                                                             const void* const* __restrict__ src_a,
                                                             const void* const* __restrict__ src_b,
                                                             float* const* __restrict__ ef_tab, float beta,
@@ -420,22 +503,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
                                                             uint16_t* __restrict__ pairs_out,
                                                             float* __restrict__ aux_out) {
     __shared__ __align__(16) SelectShared sh;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint64_t c = blockIdx.x;
-    const ChunkDesc d = chunks[c];
-    const uint32_t n_c = d.n_c;
-    const void* pa = src_a[d.tensor];
-    const void* pb = MODE == MODE_PARAMS_F32 ? src_b[d.tensor] : nullptr;
-    float* pe = ef_tab[d.tensor];
-
-    float x[16];
-    if (n_c == (uint32_t)kChunk) load_fold_full<MODE>(pa, pb, pe, d.offset, tid, beta, x);
-    else load_fold_partial<MODE>(pa, pb, pe, d.offset, tid, beta, n_c, x);
-    select_quantise_pack<QUANT>(sh, x, tid, lane, wave, n_c, kappa, force_radix, pairs_out + c * kappa,
-                                aux_out + c * kappa, aux_out + 2 * c);
-    store_ef(pe, d.offset, tid, n_c, x);
+    if (blockIdx.x >= n_gen)
+        compress_body<MODE, QUANT, true>(sh, chunks, src_a, src_b, ef_tab, beta, kappa, force_radix, pairs_out, aux_out);
+    else
+        compress_body<MODE, QUANT, false>(sh, chunks, src_a, src_b, ef_tab, beta, kappa, force_radix, pairs_out,
+                                          aux_out);
 }
 
 // Lines 1-4 for R replicas that share theta_outer (several replicas simulated on one GPU): the
@@ -444,8 +516,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
 // the outputs are those of compress_kernel.
 // Table layout (device): theta_local[r][t] at tl_tab[r * n_tensors + t], likewise ef_tab; message
 // buffers pairs_tab[r], aux_tab[r].
-template <int QUANT>
-__global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDesc* __restrict__ chunks,
+template <int QUANT, bool VEC>
+__device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so, const ChunkDesc* __restrict__ chunks,
                                                                   int n_replicas, uint32_t n_tensors,
                                                                   const float* const* __restrict__ to_tab,
                                                                   const float* const* __restrict__ tl_tab,
@@ -453,46 +525,43 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDes
                                                                   uint32_t kappa, int force_radix,
                                                                   uint16_t* const* __restrict__ pairs_tab,
                                                                   float* const* __restrict__ aux_tab) {
-    __shared__ __align__(16) SelectShared sh;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint64_t c = blockIdx.x;
-    const ChunkDesc d = chunks[c];
-    const uint32_t n_c = d.n_c;
-    const bool full = n_c == (uint32_t)kChunk;
+    const ChunkDesc d = chunks[blockIdx.x];
+    const uint64_t c = d.id;
+    const uint32_t n_c = VEC ? (uint32_t)kChunk : d.n_c;
     const float* po = to_tab[d.tensor] + d.offset;
+    const uint32_t pmask0 = VEC ? 0xFFFFu : present_mask(d, tid);
 
     // The theta_outer chunk waits in LDS (each lane re-reads only what it wrote, so no barrier is
     // needed); keeping it in registers across the replica loop would cost occupancy.
-    __shared__ __align__(16) float so[kChunk];
     float4* so4 = reinterpret_cast<float4*>(so);
-    if (full) {
+    if (VEC) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            so4[s * kThreads + tid] = stream_load(reinterpret_cast<const float4*>(po) + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) so4[s * kThreads + tid] = stream_load4(vec_at(po, d, tid, s));
     } else {
 #pragma unroll
         for (int el = 0; el < 16; ++el) {
-            uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
-            so[idx] = idx < n_c ? po[idx] : 0.f;
+            const uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+            so[idx] = (pmask0 & (1u << el)) ? po[elem_of(d, idx)] : 0.f;
         }
     }
     for (int r = 0; r < n_replicas; ++r) {
         // Per-lane index arithmetic is recomputed in every round: hoisting it out of the loop would
         // pin some 60 registers across the whole selection and halve the occupancy.
         int t = tid;
-        asm volatile("" : "+v"(t));
+        uint32_t pmask = pmask0;
+        asm volatile("" : "+v"(t), "+v"(pmask));
         const float* pl = tl_tab[(size_t)r * n_tensors + d.tensor] + d.offset;
         float* pe = ef_tab[(size_t)r * n_tensors + d.tensor];
         float x[16];
-        if (full) {
+        if (VEC) {
             float4 lv[4], ev[4];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) lv[s] = stream_load(reinterpret_cast<const float4*>(pl) + s * kThreads + t);
+            for (int s = 0; s < 4; ++s) lv[s] = stream_load4(vec_at(pl, d, t, s));
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                ev[s] = stream_load(reinterpret_cast<const float4*>(pe + d.offset) + s * kThreads + t);
+            for (int s = 0; s < 4; ++s) ev[s] = stream_load4(vec_at(pe + d.offset, d, t, s));
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const float4 ov = so4[s * kThreads + t];
@@ -504,16 +573,36 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDes
         } else {
 #pragma unroll
             for (int el = 0; el < 16; ++el) {
-                uint32_t idx = (el >> 2) * 1024 + t * 4 + (el & 3);
-                x[el] = idx < n_c ? fold(beta, pe[d.offset + idx], __fsub_rn(so[idx], pl[idx])) : 0.f;
+                const uint32_t idx = (el >> 2) * 1024 + t * 4 + (el & 3);
+                const uint32_t at = elem_of(d, idx);
+                x[el] = (pmask & (1u << el)) ? fold(beta, pe[d.offset + at], __fsub_rn(so[idx], pl[at])) : 0.f;
             }
         }
         float* aux_r = aux_tab[r];
-        select_quantise_pack<QUANT>(sh, x, t, t & 63, wave, n_c, kappa, force_radix, pairs_tab[r] + c * kappa,
-                                    aux_r + c * kappa, aux_r + 2 * c);
-        store_ef(pe, d.offset, t, n_c, x);
+        select_quantise_pack<QUANT>(sh, x, t, t & 63, wave, n_c, pmask, kappa, force_radix,
+                                    pairs_tab[r] + c * kappa, aux_r + c * kappa, aux_r + 2 * c);
+        store_ef<VEC>(pe, d, t, pmask, x);
         __syncthreads();          // every lane is done with `sh` before the next replica re-initialises it
     }
+}
+
+template <int QUANT>
+__global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n_gen,
+                                                                  int n_replicas, uint32_t n_tensors,
+                                                                  const float* const* __restrict__ to_tab,
+                                                                  const float* const* __restrict__ tl_tab,
+                                                                  float* const* __restrict__ ef_tab, float beta,
+                                                                  uint32_t kappa, int force_radix,
+                                                                  uint16_t* const* __restrict__ pairs_tab,
+                                                                  float* const* __restrict__ aux_tab) {
+    __shared__ __align__(16) SelectShared sh;
+    __shared__ __align__(16) float so[kChunk];
+    if (blockIdx.x >= n_gen)
+        compress_batch_body<QUANT, true>(sh, so, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta, kappa,
+                                         force_radix, pairs_tab, aux_tab);
+    else
+        compress_batch_body<QUANT, false>(sh, so, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta, kappa,
+                                          force_radix, pairs_tab, aux_tab);
 }
 
 // Line 5, first half: sum of the decoded messages of one chunk into a dense LDS accumulator.
@@ -563,7 +652,7 @@ __device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_
                     } else {
                         q = val[i][k];
                     }
-                    if (t < kappa_c && idx < n_c) acc[idx] = __fadd_rn(acc[idx], q);
+                    if (t < kappa_c) acc[idx] = __fadd_rn(acc[idx], q);
                 }
             }
         }
@@ -591,7 +680,7 @@ __device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uin
             } else {
                 q = ar[c * kappa + t];
             }
-            if (idx < n_c) acc[idx] = __fadd_rn(acc[idx], q);
+            acc[idx] = __fadd_rn(acc[idx], q);
         }
     }
 }
@@ -601,29 +690,27 @@ __device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uin
 //   UPDATE = 0: delta_bar = acc / M is written densely (sparseloco_aggregate).
 //   UPDATE = 1: theta = fl(theta - fl(eta * delta_bar)) is applied in the same pass; delta_bar is
 //               written only if a table for it is given (sparseloco_aggregate_update).
-template <int QUANT, int UPDATE>
-__global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __restrict__ chunks, int n_replicas,
+template <int QUANT, int UPDATE, bool VEC>
+__device__ __forceinline__ void aggregate_body(float* acc, const ChunkDesc* __restrict__ chunks, int n_replicas,
                                                              uint32_t kappa,
                                                              const uint16_t* const* __restrict__ pairs_tab,
                                                              const float* const* __restrict__ aux_tab,
                                                              float* const* __restrict__ dbar_tab,
                                                              float* const* __restrict__ theta_tab, float eta) {
-    __shared__ __align__(16) float acc[kChunk];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint64_t c = blockIdx.x;
-    const ChunkDesc d = chunks[c];
-    const uint32_t n_c = d.n_c;
+    const ChunkDesc d = chunks[blockIdx.x];
+    const uint64_t c = d.id;
+    const uint32_t n_c = VEC ? (uint32_t)kChunk : d.n_c;
     const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
-    const bool full = n_c == (uint32_t)kChunk;
     float4* acc4 = reinterpret_cast<float4*>(acc);
     float* th = UPDATE ? theta_tab[d.tensor] + d.offset : nullptr;
     float* po = dbar_tab ? dbar_tab[d.tensor] + d.offset : nullptr;
     float4 tv[4];
-    if (UPDATE && full) {
+    if (UPDATE && VEC) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) tv[s] = stream_load(reinterpret_cast<const float4*>(th) + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) tv[s] = stream_load4(vec_at(th, d, tid, s));
     }
 #pragma unroll
     for (int s = 0; s < 4; ++s) acc4[s * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -636,59 +723,85 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __
     }
     __syncthreads();
     const float m = (float)n_replicas;
-    if (full) {
+    if (VEC) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             float4 v = acc4[s * kThreads + tid];
             v.x = __fdiv_rn(v.x, m); v.y = __fdiv_rn(v.y, m); v.z = __fdiv_rn(v.z, m); v.w = __fdiv_rn(v.w, m);
-            if (po) stream_store(reinterpret_cast<float4*>(po) + s * kThreads + tid, v);
+            if (po) stream_store4(vec_at(po, d, tid, s), v);
             if (UPDATE) {
                 float4 t = tv[s];
                 t.x = __fsub_rn(t.x, __fmul_rn(eta, v.x));
                 t.y = __fsub_rn(t.y, __fmul_rn(eta, v.y));
                 t.z = __fsub_rn(t.z, __fmul_rn(eta, v.z));
                 t.w = __fsub_rn(t.w, __fmul_rn(eta, v.w));
-                stream_store(reinterpret_cast<float4*>(th) + s * kThreads + tid, t);
+                stream_store4(vec_at(th, d, tid, s), t);
             }
         }
     } else {
-        for (uint32_t idx = tid; idx < n_c; idx += kThreads) {
+        for (uint32_t idx = tid; idx < (uint32_t)kChunk; idx += kThreads) {
+            if (!present(d, idx)) continue;
+            const uint32_t at = elem_of(d, idx);
             const float v = __fdiv_rn(acc[idx], m);
-            if (po) po[idx] = v;
-            if (UPDATE) th[idx] = __fsub_rn(th[idx], __fmul_rn(eta, v));
+            if (po) po[at] = v;
+            if (UPDATE) th[at] = __fsub_rn(th[at], __fmul_rn(eta, v));
         }
     }
 }
 
+template <int QUANT, int UPDATE>
+__global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n_gen,
+                                                             int n_replicas, uint32_t kappa,
+                                                             const uint16_t* const* __restrict__ pairs_tab,
+                                                             const float* const* __restrict__ aux_tab,
+                                                             float* const* __restrict__ dbar_tab,
+                                                             float* const* __restrict__ theta_tab, float eta) {
+    __shared__ __align__(16) float acc[kChunk];
+    if (blockIdx.x >= n_gen)
+        aggregate_body<QUANT, UPDATE, true>(acc, chunks, n_replicas, kappa, pairs_tab, aux_tab, dbar_tab, theta_tab, eta);
+    else
+        aggregate_body<QUANT, UPDATE, false>(acc, chunks, n_replicas, kappa, pairs_tab, aux_tab, dbar_tab, theta_tab,
+                                             eta);
+}
+
 // Line 5, second half: theta = fl(theta - fl(eta * delta_bar)).
-__global__ __launch_bounds__(kThreads) void outer_update_kernel(const ChunkDesc* __restrict__ chunks,
-                                                                float* const* __restrict__ theta_tab,
-                                                                const float* const* __restrict__ dbar_tab,
-                                                                float eta) {
+template <bool VEC>
+__device__ __forceinline__ void outer_update_body(const ChunkDesc* __restrict__ chunks,
+                                                  float* const* __restrict__ theta_tab,
+                                                  const float* const* __restrict__ dbar_tab, float eta) {
     const int tid = threadIdx.x;
     const ChunkDesc d = chunks[blockIdx.x];
     float* th = theta_tab[d.tensor] + d.offset;
     const float* db = dbar_tab[d.tensor] + d.offset;
-    if (d.n_c == (uint32_t)kChunk) {
-        float4* th4 = reinterpret_cast<float4*>(th);
-        const float4* db4 = reinterpret_cast<const float4*>(db);
+    if (VEC) {
         float4 t[4], g[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) t[s] = stream_load(th4 + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) t[s] = stream_load4(vec_at(th, d, tid, s));
 #pragma unroll
-        for (int s = 0; s < 4; ++s) g[s] = stream_load(db4 + s * kThreads + tid);
+        for (int s = 0; s < 4; ++s) g[s] = stream_load4(vec_at(db, d, tid, s));
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             t[s].x = __fsub_rn(t[s].x, __fmul_rn(eta, g[s].x));
             t[s].y = __fsub_rn(t[s].y, __fmul_rn(eta, g[s].y));
             t[s].z = __fsub_rn(t[s].z, __fmul_rn(eta, g[s].z));
             t[s].w = __fsub_rn(t[s].w, __fmul_rn(eta, g[s].w));
-            stream_store(th4 + s * kThreads + tid, t[s]);
+            stream_store4(vec_at(th, d, tid, s), t[s]);
         }
     } else {
-        for (uint32_t idx = tid; idx < d.n_c; idx += kThreads)
-            th[idx] = __fsub_rn(th[idx], __fmul_rn(eta, db[idx]));
+        for (uint32_t idx = tid; idx < (uint32_t)kChunk; idx += kThreads) {
+            if (!present(d, idx)) continue;
+            const uint32_t at = elem_of(d, idx);
+            th[at] = __fsub_rn(th[at], __fmul_rn(eta, db[at]));
+        }
     }
+}
+
+__global__ __launch_bounds__(kThreads) void outer_update_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n_gen,
+                                                                float* const* __restrict__ theta_tab,
+                                                                const float* const* __restrict__ dbar_tab,
+                                                                float eta) {
+    if (blockIdx.x >= n_gen) outer_update_body<true>(chunks, theta_tab, dbar_tab, eta);
+    else outer_update_body<false>(chunks, theta_tab, dbar_tab, eta);
 }
 
 }  // namespace
@@ -704,7 +817,13 @@ struct sparseloco_plan {
     int64_t n_chunks = 0;
     int64_t n_params = 0;
     std::vector<int64_t> numel;
+    int layout = SPLC_LAYOUT_FLAT;
+    // Chunk table, ordered [edge chunks | complete, vector-able for fp32 only | complete, vector-able for
+    // fp32 and bf16]; every entry carries its chunk number.  The slow element-wise chunks come first so
+    // that they overlap with the streaming ones instead of forming the tail of the launch.
     ChunkDesc* d_chunks = nullptr;
+    int64_t n_gen_f32 = 0;               // entries of the first class
+    int64_t n_gen_bf16 = 0;              // entries of the first two classes
     // ring of staging slots for the per-call pointer tables
     size_t slot_bytes = 0;
     char* h_slots = nullptr;             // pinned host memory, kSlots * slot_bytes
@@ -748,28 +867,98 @@ int check_device(const sparseloco_plan* plan) {
     return dev == plan->device ? SPLC_OK : SPLC_EPLAN;
 }
 
+// Entries of the chunk table that take the element-wise path (they come first in the table).
+unsigned gen_entries(const sparseloco_plan* plan, bool bf16_source) {
+    return (unsigned)(bf16_source ? plan->n_gen_bf16 : plan->n_gen_f32);
+}
+
 template <int MODE, int QUANT>
 void launch_compress(const sparseloco_plan* plan, const void* const* a, const void* const* b, float* const* ef,
                      float beta, uint16_t* pairs_out, float* aux_out, hipStream_t stream) {
     hipLaunchKernelGGL((compress_kernel<MODE, QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
-                       plan->d_chunks, a, b, ef, beta, (uint32_t)plan->kappa,
-                       plan->select == SPLC_SELECT_RADIX ? 1 : 0, pairs_out, aux_out);
+                       plan->d_chunks, gen_entries(plan, MODE == MODE_DIRECT_BF16), a, b, ef, beta,
+                       (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, pairs_out, aux_out);
+}
+
+template <int QUANT>
+void launch_compress_batch(const sparseloco_plan* plan, int n_replicas, const float* const* to,
+                           const float* const* tl, float* const* ef, float beta, uint16_t* const* pairs,
+                           float* const* aux, hipStream_t stream) {
+    hipLaunchKernelGGL((compress_batch_kernel<QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
+                       plan->d_chunks, gen_entries(plan, false), n_replicas, (uint32_t)plan->n_tensors, to, tl, ef,
+                       beta, (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, pairs, aux);
+}
+
+template <int QUANT, int UPDATE>
+void launch_aggregate(const sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
+                      const float* const* aux, float* const* dbar, float* const* theta, float eta,
+                      hipStream_t stream) {
+    hipLaunchKernelGGL((aggregate_kernel<QUANT, UPDATE>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
+                       plan->d_chunks, gen_entries(plan, false), n_replicas, (uint32_t)plan->kappa, pairs, aux, dbar,
+                       theta, eta);
 }
 
 }  // namespace
 
 extern "C" {
 
-int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel, int kappa, int quant_mode) {
+// Chunk table of one tensor.  rows == 1 (or flat layout): runs of 4096 elements; otherwise 64 x 64 tiles
+// numbered row-major.
+static void append_chunks(std::vector<ChunkDesc>& table, uint32_t tensor, int64_t rows, int64_t cols, bool tiled) {
+    if (rows * cols == 0) return;
+    if (!tiled || rows == 1) {
+        const int64_t numel = rows * cols;
+        for (int64_t off = 0; off < numel; off += kChunk) {
+            const int64_t n = (numel - off) < kChunk ? (numel - off) : kChunk;
+            ChunkDesc cd = {};
+            cd.tensor = tensor;
+            cd.n_c = (uint32_t)n;
+            cd.offset = (uint64_t)off;
+            cd.stride = 64;
+            cd.h = (uint8_t)((n + 63) / 64);
+            cd.w = 64;
+            cd.last_w = (uint8_t)(n - 64 * (cd.h - 1));
+            cd.vec = n == kChunk ? 3 : 0;
+            table.push_back(cd);
+        }
+        return;
+    }
+    for (int64_t r0 = 0; r0 < rows; r0 += 64) {
+        for (int64_t c0 = 0; c0 < cols; c0 += 64) {
+            const int64_t h = (rows - r0) < 64 ? (rows - r0) : 64, w = (cols - c0) < 64 ? (cols - c0) : 64;
+            ChunkDesc cd = {};
+            cd.tensor = tensor;
+            cd.n_c = (uint32_t)(h * w);
+            cd.offset = (uint64_t)(r0 * cols + c0);
+            cd.stride = (uint32_t)cols;
+            cd.h = (uint8_t)h;
+            cd.w = (uint8_t)w;
+            cd.last_w = (uint8_t)w;
+            const bool full = h == 64 && w == 64;
+            cd.vec = (uint8_t)((full ? 1 : 0) | ((full && cols % 2 == 0) ? 2 : 0));
+            table.push_back(cd);
+        }
+    }
+}
+
+static int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled,
+                      int kappa, int quant_mode) {
     if (!out) return SPLC_EINVAL;
     *out = nullptr;
-    if (n_tensors < 1 || !numel || kappa < 1 || kappa > kChunk) return SPLC_EINVAL;
+    if (n_tensors < 1 || !cols || (tiled && !rows) || kappa < 1 || kappa > kChunk) return SPLC_EINVAL;
     if (quant_mode != SPLC_QUANT_NONE && quant_mode != SPLC_QUANT_2BIT) return SPLC_EINVAL;
     int64_t n_chunks = 0, n_params = 0;
     for (int i = 0; i < n_tensors; ++i) {
-        if (numel[i] < 0) return SPLC_EINVAL;
-        n_chunks += (numel[i] + kChunk - 1) / kChunk;
-        n_params += numel[i];
+        const int64_t r = tiled ? rows[i] : 1, c = cols[i];
+        if (r < 0 || c < 0) return SPLC_EINVAL;
+        if (r > 0 && c > (int64_t)0x7FFFFFFFFFFFFFFF / r) return SPLC_EINVAL;
+        if (tiled && r > 1) {
+            if (c >= (int64_t)1 << 24) return SPLC_EINVAL;        // byte offsets inside a tile must fit 32 bits
+            n_chunks += ((r + 63) / 64) * ((c + 63) / 64);
+        } else {
+            n_chunks += (r * c + kChunk - 1) / kChunk;
+        }
+        n_params += r * c;
     }
     if (n_chunks > 0x7FFFFFFF) return SPLC_EINVAL;      // one workgroup per chunk in a 1-D grid
     sparseloco_plan* plan = new (std::nothrow) sparseloco_plan();
@@ -778,20 +967,26 @@ int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* 
     plan->n_tensors = n_tensors;
     plan->kappa = kappa;
     plan->quant = quant_mode;
+    plan->layout = tiled ? SPLC_LAYOUT_TILE64 : SPLC_LAYOUT_FLAT;
     plan->n_chunks = n_chunks;
     plan->n_params = n_params;
-    plan->numel.assign(numel, numel + n_tensors);
+    plan->numel.resize((size_t)n_tensors);
 
     std::vector<ChunkDesc> table;
     table.reserve((size_t)n_chunks);
     for (int i = 0; i < n_tensors; ++i) {
-        for (int64_t off = 0; off < numel[i]; off += kChunk) {
-            ChunkDesc cd;
-            cd.tensor = (uint32_t)i;
-            cd.n_c = (uint32_t)((numel[i] - off) < kChunk ? (numel[i] - off) : kChunk);
-            cd.offset = (uint64_t)off;
-            table.push_back(cd);
-        }
+        const int64_t r = tiled ? rows[i] : 1, c = cols[i];
+        plan->numel[(size_t)i] = r * c;
+        append_chunks(table, (uint32_t)i, r, c, tiled);
+    }
+    for (size_t k = 0; k < table.size(); ++k) table[k].id = (uint32_t)k;
+    std::stable_sort(table.begin(), table.end(), [](const ChunkDesc& a, const ChunkDesc& b) {
+        auto cls = [](const ChunkDesc& d) { return d.vec == 0 ? 0 : (d.vec == 1 ? 1 : 2); };
+        return cls(a) < cls(b);
+    });
+    for (const ChunkDesc& cd : table) {
+        plan->n_gen_f32 += cd.vec == 0;
+        plan->n_gen_bf16 += cd.vec != 3;
     }
     int rc = SPLC_OK;
     // largest pointer table of any call: aggregate (2 per replica + 2 per tensor), compress (3 per
@@ -824,6 +1019,15 @@ int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* 
     return SPLC_OK;
 }
 
+int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel, int kappa, int quant_mode) {
+    return plan_build(out, n_tensors, nullptr, numel, false, kappa, quant_mode);
+}
+
+int sparseloco_plan_create_2d(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols,
+                              int kappa, int quant_mode) {
+    return plan_build(out, n_tensors, rows, cols, true, kappa, quant_mode);
+}
+
 void sparseloco_plan_destroy(sparseloco_plan* plan) {
     if (!plan) return;
     for (int s = 0; s < kSlots; ++s) {
@@ -842,6 +1046,7 @@ int64_t sparseloco_plan_num_chunks(const sparseloco_plan* plan) { return plan ? 
 int64_t sparseloco_plan_num_params(const sparseloco_plan* plan) { return plan ? plan->n_params : SPLC_EINVAL; }
 int sparseloco_plan_kappa(const sparseloco_plan* plan) { return plan ? plan->kappa : SPLC_EINVAL; }
 int sparseloco_plan_quant_mode(const sparseloco_plan* plan) { return plan ? plan->quant : SPLC_EINVAL; }
+int sparseloco_plan_layout(const sparseloco_plan* plan) { return plan ? plan->layout : SPLC_EINVAL; }
 
 int sparseloco_plan_set_select(sparseloco_plan* plan, int select_mode) {
     if (!plan || (select_mode != SPLC_SELECT_AUTO && select_mode != SPLC_SELECT_RADIX)) return SPLC_EINVAL;
@@ -866,12 +1071,12 @@ int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype, co
         return SPLC_EINVAL;
     }
     if (!(beta == beta) || beta - beta != 0.f) return SPLC_EINVAL;      // finite
-    const size_t src_align = mode == MODE_DIRECT_BF16 ? 8 : 16;
+    const size_t src_align = 4;          // natural for fp32; for bf16 it keeps vector rows dword aligned
     for (int i = 0; i < plan->n_tensors; ++i) {
         if (plan->numel[i] == 0) continue;
         if (!src_a[i] || !ef[i] || (mode == MODE_PARAMS_F32 && !src_b[i])) return SPLC_EINVAL;
-        if (!aligned(src_a[i], src_align) || !aligned(ef[i], 16) ||
-            (mode == MODE_PARAMS_F32 && !aligned(src_b[i], 16)))
+        if (!aligned(src_a[i], src_align) || !aligned(ef[i], 4) ||
+            (mode == MODE_PARAMS_F32 && !aligned(src_b[i], 4)))
             return SPLC_EALIGN;
     }
     if (!aligned(pairs_out, 2) || !aligned(aux_out, 4)) return SPLC_EALIGN;
@@ -927,10 +1132,10 @@ int sparseloco_compress_batch(sparseloco_plan* plan, int n_replicas, const float
     for (int i = 0; i < plan->n_tensors; ++i) {
         if (plan->numel[i] == 0) continue;
         if (!theta_outer[i]) return SPLC_EINVAL;
-        if (!aligned(theta_outer[i], 16)) return SPLC_EALIGN;
+        if (!aligned(theta_outer[i], 4)) return SPLC_EALIGN;
         for (int r = 0; r < n_replicas; ++r) {
             if (!theta_local[r][i] || !ef[r][i]) return SPLC_EINVAL;
-            if (!aligned(theta_local[r][i], 16) || !aligned(ef[r][i], 16)) return SPLC_EALIGN;
+            if (!aligned(theta_local[r][i], 4) || !aligned(ef[r][i], 4)) return SPLC_EALIGN;
         }
     }
     int rc = check_device(plan);
@@ -961,14 +1166,10 @@ int sparseloco_compress_batch(sparseloco_plan* plan, int n_replicas, const float
     float* const* d_ef = reinterpret_cast<float* const*>(dtab + (nt + nr * nt) * sizeof(void*));
     uint16_t* const* d_pairs = reinterpret_cast<uint16_t* const*>(dtab + (nt + 2 * nr * nt) * sizeof(void*));
     float* const* d_aux = reinterpret_cast<float* const*>(dtab + (nt + 2 * nr * nt + nr) * sizeof(void*));
-    const dim3 grid((unsigned)plan->n_chunks), block(kThreads);
-    const int force = plan->select == SPLC_SELECT_RADIX ? 1 : 0;
     if (plan->quant == SPLC_QUANT_2BIT)
-        hipLaunchKernelGGL((compress_batch_kernel<SPLC_QUANT_2BIT>), grid, block, 0, st, plan->d_chunks, n_replicas,
-                           (uint32_t)nt, d_to, d_tl, d_ef, beta, (uint32_t)plan->kappa, force, d_pairs, d_aux);
+        launch_compress_batch<SPLC_QUANT_2BIT>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
     else
-        hipLaunchKernelGGL((compress_batch_kernel<SPLC_QUANT_NONE>), grid, block, 0, st, plan->d_chunks, n_replicas,
-                           (uint32_t)nt, d_to, d_tl, d_ef, beta, (uint32_t)plan->kappa, force, d_pairs, d_aux);
+        launch_compress_batch<SPLC_QUANT_NONE>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
     if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
     return slot_release(plan, slot, st);
 }
@@ -988,11 +1189,11 @@ static int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t*
         if (plan->numel[i] == 0) continue;
         if (delta_bar_out) {
             if (!delta_bar_out[i]) return SPLC_EINVAL;
-            if (!aligned(delta_bar_out[i], 16)) return SPLC_EALIGN;
+            if (!aligned(delta_bar_out[i], 4)) return SPLC_EALIGN;
         }
         if (update) {
             if (!theta_outer[i]) return SPLC_EINVAL;
-            if (!aligned(theta_outer[i], 16)) return SPLC_EALIGN;
+            if (!aligned(theta_outer[i], 4)) return SPLC_EALIGN;
         }
     }
     int rc = check_device(plan);
@@ -1020,21 +1221,11 @@ static int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t*
     float* const* dout =
         delta_bar_out ? reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*)) : nullptr;
     float* const* dth = reinterpret_cast<float* const*>(dtab + (2 * nr + nt) * sizeof(void*));
-    const dim3 grid((unsigned)plan->n_chunks), block(kThreads);
-    const uint32_t kappa = (uint32_t)plan->kappa;
     const bool q2 = plan->quant == SPLC_QUANT_2BIT;
-    if (q2 && !update)
-        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_2BIT, 0>), grid, block, 0, st, plan->d_chunks, n_replicas,
-                           kappa, dp, dx, dout, dth, outer_lr);
-    else if (q2)
-        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_2BIT, 1>), grid, block, 0, st, plan->d_chunks, n_replicas,
-                           kappa, dp, dx, dout, dth, outer_lr);
-    else if (!update)
-        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_NONE, 0>), grid, block, 0, st, plan->d_chunks, n_replicas,
-                           kappa, dp, dx, dout, dth, outer_lr);
-    else
-        hipLaunchKernelGGL((aggregate_kernel<SPLC_QUANT_NONE, 1>), grid, block, 0, st, plan->d_chunks, n_replicas,
-                           kappa, dp, dx, dout, dth, outer_lr);
+    if (q2 && !update) launch_aggregate<SPLC_QUANT_2BIT, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
+    else if (q2) launch_aggregate<SPLC_QUANT_2BIT, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
+    else if (!update) launch_aggregate<SPLC_QUANT_NONE, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
+    else launch_aggregate<SPLC_QUANT_NONE, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
     if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
     return slot_release(plan, slot, st);
 }
@@ -1057,7 +1248,7 @@ int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer, co
     for (int i = 0; i < plan->n_tensors; ++i) {
         if (plan->numel[i] == 0) continue;
         if (!theta_outer[i] || !delta_bar[i]) return SPLC_EINVAL;
-        if (!aligned(theta_outer[i], 16) || !aligned(delta_bar[i], 16)) return SPLC_EALIGN;
+        if (!aligned(theta_outer[i], 4) || !aligned(delta_bar[i], 4)) return SPLC_EALIGN;
     }
     int rc = check_device(plan);
     if (rc != SPLC_OK) return rc;
@@ -1078,7 +1269,7 @@ int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer, co
     float* const* dth = reinterpret_cast<float* const*>(dtab);
     const float* const* ddb = reinterpret_cast<const float* const*>(dtab + nt * sizeof(void*));
     hipLaunchKernelGGL(outer_update_kernel, dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, st, plan->d_chunks,
-                       dth, ddb, outer_lr);
+                       gen_entries(plan, false), dth, ddb, outer_lr);
     if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
     return slot_release(plan, slot, st);
 }

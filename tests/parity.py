@@ -29,6 +29,7 @@ def to_np(t: torch.Tensor) -> np.ndarray:
 
 
 def assert_close_fp32(got: np.ndarray, want: np.ndarray, what: str):
+    got, want = got.reshape(-1), want.reshape(-1)
     assert got.shape == want.shape, what
     assert np.allclose(got, want, rtol=RTOL, atol=ATOL), what
     # stronger than the stated tolerance: equal as numbers (only the sign of a zero may differ)
@@ -41,7 +42,9 @@ class HostCase:
     """Inputs on the host: theta_outer[t]; per replica theta_local[r][t] (fp32) or
     delta[r][t] (fp32, or uint16 holding bf16 bits); ef[r][t]."""
 
-    def __init__(self, theta_outer, ef, theta_local=None, delta=None):
+    def __init__(self, theta_outer, ef, theta_local=None, delta=None, shapes=None):
+        # shapes: per tensor (rows, cols) etc. for the tiled layout; None = flat chunks
+        self.shapes = None if shapes is None else [tuple(s) for s in shapes]
         self.theta_outer = [np.ascontiguousarray(x, np.float32).reshape(-1) for x in theta_outer]
         self.ef = [[np.ascontiguousarray(x, np.float32).reshape(-1) for x in r] for r in ef]
         self.theta_local = None if theta_local is None else \
@@ -52,6 +55,8 @@ class HostCase:
 
 
 def run_oracle(case: HostCase, kappa, beta, lr, quant=True, outer_steps=1, deltas_per_step=None):
+    geo = dict(shapes=case.shapes, tile=64) if case.shapes is not None else {}
+    shapes = case.shapes if case.shapes is not None else case.numels
     th = [x.copy() for x in case.theta_outer]
     ef = [[x.copy() for x in r] for r in case.ef]
     out = []
@@ -60,12 +65,13 @@ def run_oracle(case: HostCase, kappa, beta, lr, quant=True, outer_steps=1, delta
         for r in range(case.R):
             if case.delta is not None:
                 d = case.delta[r] if deltas_per_step is None else deltas_per_step[step][r]
-                p, a = oracle.compress(ef[r], kappa, beta, delta=d, quant=quant)
+                p, a = oracle.compress(ef[r], kappa, beta, delta=d, quant=quant, **geo)
             else:
                 p, a = oracle.compress(ef[r], kappa, beta, theta_outer=th, theta_local=case.theta_local[r],
-                                       quant=quant)
+                                       quant=quant, **geo)
             pairs.append(p), aux.append(a)
-        dbar = oracle.aggregate(case.numels, pairs, aux, kappa, quant=quant)
+        dbar = oracle.aggregate(shapes, pairs, aux, kappa, quant=quant,
+                                tile=64 if case.shapes is not None else None)
         oracle.outer_update(th, dbar, lr)
         out.append(dict(pairs=pairs, aux=aux, ef=[[x.copy() for x in r] for r in ef], dbar=dbar,
                         theta=[x.copy() for x in th]))
@@ -83,7 +89,8 @@ def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AU
     """fused: None = aggregate then outer_update; "with_mean" / "no_mean" = sparseloco_aggregate_update
     with / without the dense mean output (without it, the returned mean is recomputed by a separate
     sparseloco_aggregate call, which the fused call must agree with anyway)."""
-    plan = B.Plan(case.numels, kappa, quant)
+    plan = B.Plan(case.shapes if case.shapes is not None else case.numels, kappa, quant,
+                  tiled=case.shapes is not None)
     plan.set_select(select)
     th = [_dev(x) for x in case.theta_outer]
     ef = [[_dev(x) for x in r] for r in case.ef]

@@ -21,17 +21,26 @@ pytestmark = pytest.mark.gpu
 CH = 4096
 
 
-def sample_chunks(numels, n_random, seed):
+def chunks_of(shape, tiled):
+    rows, cols = B.rows_cols(shape)
+    if tiled and rows > 1:
+        return ((rows + 63) // 64) * ((cols + 63) // 64)
+    return (rows * cols + CH - 1) // CH
+
+
+def sample_chunks(shapes, n_random, seed, tiled=False):
     rng = np.random.default_rng(seed)
     picks = []                                   # (tensor, chunk-in-tensor)
-    for t, n in enumerate(numels):
-        nc = (n + CH - 1) // CH
+    total = [chunks_of(s, tiled) for s in shapes]
+    for t, nc in enumerate(total):
         if nc == 0:
             continue
         picks.append((t, 0))
         if nc > 1:
             picks.append((t, nc - 1))
-    total = [(n + CH - 1) // CH for n in numels]
+        if tiled and B.rows_cols(shapes[t])[0] > 1:          # right edge of the first tile row, left edge of the last
+            nbj = (B.rows_cols(shapes[t])[1] + 63) // 64
+            picks += [(t, nbj - 1), (t, nc - nbj)]
     cum = np.cumsum([0] + total)
     for g in rng.integers(0, cum[-1], n_random):
         t = int(np.searchsorted(cum, g, side="right") - 1)
@@ -39,11 +48,19 @@ def sample_chunks(numels, n_random, seed):
     return sorted(set(picks)), cum
 
 
-def gather(tensors, picks):
+def gather(tensors, picks, shapes=None):
+    """The picked chunks as host arrays; with shapes (tiled layout) a 2-D tensor's chunk is its 64 x 64 tile."""
     out = []
     for t, c in picks:
         flat = tensors[t].view(-1)
-        out.append(parity.to_np(flat[c * CH:min((c + 1) * CH, flat.numel())]))
+        rows, cols = B.rows_cols(shapes[t]) if shapes is not None else (1, flat.numel())
+        if rows > 1:
+            nbj = (cols + 63) // 64
+            bi, bj = c // nbj, c % nbj
+            tile = flat.view(rows, cols)[bi * 64:(bi + 1) * 64, bj * 64:(bj + 1) * 64]
+            out.append(parity.to_np(tile.contiguous()))
+        else:
+            out.append(parity.to_np(flat[c * CH:min((c + 1) * CH, flat.numel())]).reshape(1, -1))
     return out
 
 
@@ -56,7 +73,7 @@ def gather_msg(msg, picks, cum, kappa, quant=True):
 
 
 def all_chunk_properties(plan, msg, numels, kappa):
-    """Every chunk: exactly kappa_c valid pairs, ascending in-range indices, spare bits zero, lo <= hi."""
+    """Every chunk (flat layout): exactly kappa_c valid pairs, ascending in-range indices, spare bits zero, lo <= hi."""
     p, a = msg
     total = [(n + CH - 1) // CH for n in numels]
     n_c = torch.full((sum(total),), CH, dtype=torch.int32, device=p.device)
@@ -78,13 +95,15 @@ def all_chunk_properties(plan, msg, numels, kappa):
     assert bool((s[:, 0] <= s[:, 1]).all()) and bool((s[:, 0] >= 0).all()) and bool(torch.isfinite(s).all())
 
 
-def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1, seed=0):
+def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1, seed=0, tiled=False):
     cfg = W.WORKLOADS[workload]
     rs = W.ReplicaSet(workload, device="cuda", replicas=R, tensors=tensors)
-    picks, cum = sample_chunks(rs.numels, n_random, seed)
-    th0 = gather(rs.theta_outer, picks)
-    ef0 = [gather(rs.ef[r], picks) for r in range(R)]
-    plan = B.Plan(rs.numels, kappa, True)
+    shapes = [W.tensor_shapes(workload)[t] for t in rs.tensor_ids] if tiled else None
+    picks, cum = sample_chunks(shapes if tiled else rs.numels, n_random, seed, tiled)
+    gather_ = lambda tensors, picks: gather(tensors, picks, shapes)
+    th0 = gather_(rs.theta_outer, picks)
+    ef0 = [gather_(rs.ef[r], picks) for r in range(R)]
+    plan = B.Plan(shapes if tiled else rs.numels, kappa, True, tiled=tiled)
     dbar = [torch.empty(n, device="cuda") for n in rs.numels]
     got, deltas_per_step = [], []
     tl0 = None
@@ -94,9 +113,9 @@ def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1
                 for r in range(R):
                     for i, t in enumerate(rs.tensor_ids):
                         rs.delta[r][i] = W.replica_inputs(workload, t, r, None, "cuda", outer_step=step)[1]
-            deltas_per_step.append([gather(rs.delta[r], picks) for r in range(R)])
+            deltas_per_step.append([gather_(rs.delta[r], picks) for r in range(R)])
         elif step == 0:
-            tl0 = [gather(rs.theta_local[r], picks) for r in range(R)]
+            tl0 = [gather_(rs.theta_local[r], picks) for r in range(R)]
         msgs = [plan.message_buffers() for _ in range(R)]
         for r in range(R):
             if rs.direct:
@@ -108,18 +127,20 @@ def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1
         B.sparseloco_outer_update(plan, rs.theta_outer, dbar, cfg["outer_lr"])
         torch.cuda.synchronize()
         for r in (0, R - 1):
-            all_chunk_properties(plan, msgs[r], rs.numels, kappa)
+            if not tiled:
+                all_chunk_properties(plan, msgs[r], rs.numels, kappa)
         gm = [gather_msg(msgs[r], picks, cum, kappa) for r in range(R)]
         got.append(dict(pairs=[g[0] for g in gm], aux=[g[1] for g in gm],
-                        ef=[gather(rs.ef[r], picks) for r in range(R)],
-                        dbar=gather(dbar, picks), theta=gather(rs.theta_outer, picks)))
+                        ef=[gather_(rs.ef[r], picks) for r in range(R)],
+                        dbar=gather_(dbar, picks), theta=gather_(rs.theta_outer, picks)))
         del msgs
     plan.close()
+    sample_shapes = [x.shape for x in th0] if tiled else None      # every sampled tile is one tile of its own
     if rs.direct:
-        case = parity.HostCase(th0, ef0, delta=deltas_per_step[0])
+        case = parity.HostCase(th0, ef0, delta=deltas_per_step[0], shapes=sample_shapes)
         want = parity.run_oracle(case, kappa, cfg["beta"], cfg["outer_lr"], True, outer_steps, deltas_per_step)
     else:
-        case = parity.HostCase(th0, ef0, theta_local=tl0)
+        case = parity.HostCase(th0, ef0, theta_local=tl0, shapes=sample_shapes)
         want = parity.run_oracle(case, kappa, cfg["beta"], cfg["outer_lr"], True, outer_steps)
     parity.compare(got, want, "workload %d full size (%d sampled chunks)" % (workload, len(picks)))
 
@@ -145,3 +166,14 @@ def test_workload4_ragged_bf16_two_outer_steps():
 
 def test_workload4_all_replicas_on_two_layers():
     fullsize_check(4, 32, W.WORKLOADS[4]["kappa"], tensors=list(range(18)) + [144, 145], n_random=100)
+
+
+def test_workload2_full_size_tiled_layout():
+    """The ~0.9B set with 64 x 64 tile chunks (every matrix dimension is a multiple of 64; vectors stay flat)."""
+    cfg = W.WORKLOADS[2]
+    fullsize_check(2, 4, cfg["kappa"], n_random=300, tiled=True)
+
+
+def test_workload4_ragged_shapes_tiled_layout():
+    """2050 x 5630 and 32001 x 2048 matrices: edge tiles on both sides, odd row starts for the bf16 source."""
+    fullsize_check(4, 2, W.WORKLOADS[4]["kappa"], tensors=list(range(9)) + [144, 145], n_random=200, tiled=True)

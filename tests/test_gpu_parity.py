@@ -16,7 +16,13 @@ pytestmark = pytest.mark.gpu
 RAGGED = [4096 * 5, 4096 * 3 + 17, 100, 4096, 1, 2047, 4096 * 2 + 4, 0, 4096 * 2 - 1]
 
 
-def gaussian_case(numels, R, seed, direct=None, heavy=False):
+TILED_SHAPES = [(128, 192), (130, 70), (64, 64), (1, 5000), (63, 65), (200, 3), (3, 200), (65, 129), (1, 1), (70, 66)]
+
+
+def gaussian_case(numels, R, seed, direct=None, heavy=False, shapes=None):
+    """shapes: run with the 64 x 64 tile layout over these (rows, cols) matrices instead of flat chunks."""
+    if shapes is not None:
+        numels = [r * c for r, c in shapes]
     rng = np.random.default_rng(seed)
     draw = (lambda n: rng.standard_t(3, n)) if heavy else (lambda n: rng.standard_normal(n))
     th = [(rng.standard_normal(n) * 0.02).astype(np.float32) for n in numels]
@@ -24,10 +30,10 @@ def gaussian_case(numels, R, seed, direct=None, heavy=False):
     deltas = [[(draw(n) * 1e-3).astype(np.float32) for n in numels] for _ in range(R)]
     if direct is None:
         tl = [[(th[t] - deltas[r][t]).astype(np.float32) for t in range(len(numels))] for r in range(R)]
-        return parity.HostCase(th, ef, theta_local=tl)
+        return parity.HostCase(th, ef, theta_local=tl, shapes=shapes)
     if direct == "bf16":
         deltas = [[(d.view(np.uint32) >> 16).astype(np.uint16) for d in r] for r in deltas]
-    return parity.HostCase(th, ef, delta=deltas)
+    return parity.HostCase(th, ef, delta=deltas, shapes=shapes)
 
 
 @pytest.mark.parametrize("select", [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX])
@@ -35,6 +41,53 @@ def gaussian_case(numels, R, seed, direct=None, heavy=False):
 def test_ragged_tensor_list_params_mode(kappa, select):
     case = gaussian_case(RAGGED, R=3, seed=kappa)
     parity.check(case, kappa, select=select, what="ragged kappa=%d" % kappa)
+
+
+@pytest.mark.parametrize("select", [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX])
+@pytest.mark.parametrize("kappa", [1, 32, 64, 200, 4096])
+def test_tiled_layout_params_mode(kappa, select):
+    """64 x 64 tiles: full tiles, edge tiles on both sides, column counts that are odd or not
+    multiples of four, 1-D tensors, tiles smaller than kappa."""
+    case = gaussian_case(None, R=3, seed=300 + kappa, shapes=TILED_SHAPES)
+    parity.check(case, kappa, select=select, what="tiled kappa=%d" % kappa)
+
+
+@pytest.mark.parametrize("direct,quant", [("f32", True), ("bf16", True), ("bf16", False)])
+def test_tiled_layout_direct_modes(direct, quant):
+    case = gaussian_case(None, R=2, seed=331, direct=direct, heavy=True, shapes=TILED_SHAPES)
+    parity.check(case, 32, quant=quant, fused="no_mean", outer_steps=2, what="tiled direct %s" % direct)
+
+
+def test_tiled_layout_batched_and_fused():
+    case = gaussian_case(None, R=5, seed=337, shapes=TILED_SHAPES)
+    parity.check(case, 64, batch=True, fused="with_mean", outer_steps=2, what="tiled batched")
+
+
+def test_four_byte_aligned_views():
+    """Tensor pointers need only 4-byte alignment: views that start one element into an allocation."""
+    import torch
+    from paper_2601_02360_amd import binding
+    rng = np.random.default_rng(41)
+    n = 4096 * 3 + 10
+    host = [(rng.standard_normal(n) * s).astype(np.float32) for s in (0.02, 0.02, 1e-4)]
+    host[1] = (host[0] - (rng.standard_normal(n) * 1e-3).astype(np.float32)).astype(np.float32)
+    case = parity.HostCase([host[0]], [[host[2]]], theta_local=[[host[1]]])
+    want = parity.run_oracle(case, 32, 0.95, 1.0)
+    bufs = [torch.zeros(n + 1, device="cuda") for _ in range(4)]
+    views = [b[1:] for b in bufs]
+    for v, h in zip(views, host):
+        v.copy_(torch.from_numpy(h))
+    assert all(v.data_ptr() % 16 == 4 for v in views)
+    plan = binding.Plan([n], 32)
+    p, a = plan.message_buffers()
+    binding.sparseloco_compress(plan, [views[2]], p, a, 0.95, theta_outer=[views[0]], theta_local=[views[1]])
+    binding.sparseloco_aggregate(plan, [p], [a], [views[3]])
+    binding.sparseloco_outer_update(plan, [views[0]], [views[3]], 1.0)
+    torch.cuda.synchronize()
+    got = [dict(pairs=[parity.to_np(p)], aux=[parity.to_np(a)], ef=[[parity.to_np(views[2])]],
+                dbar=[parity.to_np(views[3])], theta=[parity.to_np(views[0])])]
+    parity.compare(got, want, "4-byte aligned views")
+    plan.close()
 
 
 @pytest.mark.parametrize("quant", [True, False])
@@ -153,9 +206,9 @@ def test_error_returns_do_not_launch():
     with pytest.raises(B.SparseLoCoError) as ei:
         B.sparseloco_compress(plan, e, p, a, 0.95, theta_outer=e, theta_local=[e[0], None])
     assert ei.value.status == B.SPLC_EINVAL
-    big = torch.zeros(4096 + 8, device="cuda")
-    with pytest.raises(B.SparseLoCoError) as ei:
-        B.sparseloco_compress(plan, [big[1:4097], e[1]], p, a, 0.95, delta=e)
+    big = torch.zeros(2 * (4096 + 8), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(B.SparseLoCoError) as ei:        # a bf16 source that starts at an odd element: 2-byte aligned
+        B.sparseloco_compress(plan, e, p, a, 0.95, delta=[big[1:4097], big[4100:4110]])
     assert ei.value.status == B.SPLC_EALIGN
     with pytest.raises(B.SparseLoCoError) as ei:
         B.sparseloco_compress(plan, e, p, a, float("inf"), delta=e)
