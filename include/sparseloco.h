@@ -179,11 +179,16 @@ int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer,
  * sparseloco_outer_update, bit-identical to calling the two in sequence, without
  * the round trip of delta_bar through memory.  theta_outer[n_tensors] is updated
  * in place.  delta_bar_out may be NULL; if given, the dense mean is written too.
+ * The next inner phase starts every replica from the synchronised parameters
+ * (section 2.1, inner step): if n_reset > 0, the new theta_outer is also written
+ * into theta_local_reset[r][n_tensors] for r < n_reset (0 <= n_reset <= 64;
+ * host array of host arrays of device pointers; NULL if n_reset == 0).
  */
 int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas,
                                 const uint16_t* const* pairs, const float* const* aux,
                                 float* const* theta_outer, float outer_lr,
-                                float* const* delta_bar_out, void* stream);
+                                float* const* delta_bar_out,
+                                int n_reset, float* const* const* theta_local_reset, void* stream);
 
 const char* sparseloco_strerror(int status);
 

@@ -76,7 +76,7 @@ def lib():
         L.sparseloco_outer_update.restype = i32
         L.sparseloco_outer_update.argtypes = [vp, pp, pp, f32, vp]
         L.sparseloco_aggregate_update.restype = i32
-        L.sparseloco_aggregate_update.argtypes = [vp, i32, pp, pp, pp, f32, pp, vp]
+        L.sparseloco_aggregate_update.argtypes = [vp, i32, pp, pp, pp, f32, pp, i32, ctypes.POINTER(pp), vp]
         L.sparseloco_compress_batch.restype = i32
         L.sparseloco_compress_batch.argtypes = [vp, i32, pp, ctypes.POINTER(pp), ctypes.POINTER(pp), f32, pp, pp, vp]
         L.sparseloco_strerror.restype = ctypes.c_char_p
@@ -214,12 +214,16 @@ def sparseloco_outer_update(plan: Plan, theta_outer, delta_bar, outer_lr: float,
 
 
 def sparseloco_aggregate_update(plan: Plan, pairs, aux, theta_outer, outer_lr: float, *, delta_bar_out=None,
-                                stream=None) -> None:
-    """Mean over replicas and outer update in one pass (theta_outer in place); delta_bar_out optional."""
+                                reset=None, stream=None) -> None:
+    """Mean over replicas and outer update in one pass (theta_outer in place); delta_bar_out optional;
+    reset: per replica a list of theta_local tensors (or a ptr_table_2d) that receive the new theta_outer."""
     pt, at = _table(pairs), _table(aux)
+    rt = None
+    if reset is not None:
+        rt = reset if isinstance(reset, ctypes.Array) and hasattr(reset, "_keepalive") else ptr_table_2d(reset)
     rc = lib().sparseloco_aggregate_update(plan.handle, len(pt), pt, at, _table(theta_outer), float(outer_lr),
                                            None if delta_bar_out is None else _table(delta_bar_out),
-                                           _stream(stream))
+                                           0 if rt is None else len(rt), rt, _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_aggregate_update")
 

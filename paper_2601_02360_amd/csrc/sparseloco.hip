@@ -304,23 +304,24 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
     if (tid == 0) sh.ncand = 0;
 
     bool selected_by_filter = false;
-    if (n_c == (uint32_t)kChunk && kappa <= (uint32_t)kFilterKappaMax && !force_radix) {
+    if (kappa <= (uint32_t)kFilterKappaMax && !force_radix) {
         // ---- candidate filter: a lower bound T0 of the threshold from the lane maxima ----
         uint32_t key[16];
 #pragma unroll
         for (int el = 0; el < 16; ++el) key[el] = __float_as_uint(x[el]) & 0x7FFFFFFFu;
-        uint32_t tmax = key[0];
+        uint32_t tmax = 0;
 #pragma unroll
-        for (int el = 1; el < 16; ++el) tmax = key[el] > tmax ? key[el] : tmax;
-        // Largest X (low 10 bits zero) with at least m lane maxima >= X in this wave.  Each of those
-        // lanes holds a distinct element >= X, so over four waves at least 4*m >= kappa elements are
-        // >= min X: the threshold cannot be below it.
-        const uint32_t m = (kappa + 3) >> 2;
+        for (int el = 0; el < 16; ++el) tmax = ((pmask >> el) & 1u) && key[el] > tmax ? key[el] : tmax;
+        // Largest X (low 10 bits zero) with at least m lanes of this wave that hold a present element
+        // >= X.  Those elements are distinct, so over four waves at least 4*m >= kappa_c elements are
+        // >= min X: the threshold cannot be below it.  A wave with fewer than m non-empty lanes (edge
+        // chunks) leaves X = 0, which makes every present element a candidate.
+        const uint32_t m = (kappa_c + 3) >> 2;
         uint32_t X = 0;
 #pragma unroll
         for (int b = 30; b >= 10; --b) {
             uint32_t t = X | (1u << b);
-            uint32_t cnt = (uint32_t)__popcll(__ballot(tmax >= t));
+            uint32_t cnt = (uint32_t)__popcll(__ballot(pmask != 0 && tmax >= t));
             X = cnt >= m ? t : X;
         }
         if (lane == 0) sh.t0[wave] = X;
@@ -330,12 +331,12 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
         T0 = sh.t0[2] < T0 ? sh.t0[2] : T0;
         T0 = sh.t0[3] < T0 ? sh.t0[3] : T0;
 
-        // ---- compact the candidates (key >= T0) into LDS, wave by wave ----
+        // ---- compact the candidates (present, key >= T0) into LDS, wave by wave ----
         uint64_t msk[16];
         uint32_t cnt = 0;
 #pragma unroll
         for (int el = 0; el < 16; ++el) {
-            msk[el] = __ballot(key[el] >= T0);
+            msk[el] = __ballot(((pmask >> el) & 1u) && key[el] >= T0);
             cnt += (uint32_t)__popcll(msk[el]);
         }
         uint32_t base = 0;
@@ -346,7 +347,7 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
 #pragma unroll
             for (int el = 0; el < 16; ++el) {
                 if (msk[el] != 0) {
-                    if (key[el] >= T0) {
+                    if (((pmask >> el) & 1u) && key[el] >= T0) {
                         uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
                         sh.cand[run + lanes_below(msk[el])] = ((uint64_t)key[el] << 12) | (uint64_t)(4095u - idx);
                     }
@@ -365,9 +366,9 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
                     uint64_t c0 = sh.cand[i], c1 = sh.cand[i + 1];
                     rank += (c0 > mine ? 1u : 0u) + (c1 > mine ? 1u : 0u);
                 }
-                if (rank == kappa - 1) sh.thr = mine;
+                if (rank == kappa_c - 1) sh.thr = mine;
                 if (rank == 0) sh.wmax[0] = (uint32_t)(mine >> 12);
-                if (rank < kappa) atomicAdd(&sh.bucket[(4095u - ((uint32_t)mine & 4095u)) >> 8], 1u);
+                if (rank < kappa_c) atomicAdd(&sh.bucket[(4095u - ((uint32_t)mine & 4095u)) >> 8], 1u);
             }
             selected_by_filter = true;
         }
@@ -688,7 +689,9 @@ __device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uin
 // Line 5 of the update equations.  One workgroup per chunk; all lanes clear the 16 KB LDS
 // accumulator, wave 0 applies the messages, all lanes divide once by M and write.
 //   UPDATE = 0: delta_bar = acc / M is written densely (sparseloco_aggregate).
-//   UPDATE = 1: theta = fl(theta - fl(eta * delta_bar)) is applied in the same pass; delta_bar is
+//   UPDATE = 1: theta = fl(theta - fl(eta * delta_bar)) is applied in the same pass, and the new theta
+//               is also copied into n_reset further parameter sets (the replicas' theta_local, which
+//               restart from the synchronised parameters: section 2.1, inner step); delta_bar is
 //               written only if a table for it is given (sparseloco_aggregate_update).
 template <int QUANT, int UPDATE, bool VEC>
 __device__ __forceinline__ void aggregate_body(float* acc, const ChunkDesc* __restrict__ chunks, int n_replicas,
@@ -696,7 +699,8 @@ __device__ __forceinline__ void aggregate_body(float* acc, const ChunkDesc* __re
                                                              const uint16_t* const* __restrict__ pairs_tab,
                                                              const float* const* __restrict__ aux_tab,
                                                              float* const* __restrict__ dbar_tab,
-                                                             float* const* __restrict__ theta_tab, float eta) {
+                                                             float* const* __restrict__ theta_tab, float eta, int n_reset,
+                                               uint32_t n_tensors, float* const* __restrict__ reset_tab) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -736,6 +740,8 @@ __device__ __forceinline__ void aggregate_body(float* acc, const ChunkDesc* __re
                 t.z = __fsub_rn(t.z, __fmul_rn(eta, v.z));
                 t.w = __fsub_rn(t.w, __fmul_rn(eta, v.w));
                 stream_store4(vec_at(th, d, tid, s), t);
+                for (int r = 0; r < n_reset; ++r)
+                    stream_store4(vec_at(reset_tab[(size_t)r * n_tensors + d.tensor] + d.offset, d, tid, s), t);
             }
         }
     } else {
@@ -744,7 +750,11 @@ __device__ __forceinline__ void aggregate_body(float* acc, const ChunkDesc* __re
             const uint32_t at = elem_of(d, idx);
             const float v = __fdiv_rn(acc[idx], m);
             if (po) po[at] = v;
-            if (UPDATE) th[at] = __fsub_rn(th[at], __fmul_rn(eta, v));
+            if (UPDATE) {
+                const float t = __fsub_rn(th[at], __fmul_rn(eta, v));
+                th[at] = t;
+                for (int r = 0; r < n_reset; ++r) reset_tab[(size_t)r * n_tensors + d.tensor][d.offset + at] = t;
+            }
         }
     }
 }
@@ -755,13 +765,16 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __
                                                              const uint16_t* const* __restrict__ pairs_tab,
                                                              const float* const* __restrict__ aux_tab,
                                                              float* const* __restrict__ dbar_tab,
-                                                             float* const* __restrict__ theta_tab, float eta) {
+                                                             float* const* __restrict__ theta_tab, float eta,
+                                                             int n_reset, uint32_t n_tensors,
+                                                             float* const* __restrict__ reset_tab) {
     __shared__ __align__(16) float acc[kChunk];
     if (blockIdx.x >= n_gen)
-        aggregate_body<QUANT, UPDATE, true>(acc, chunks, n_replicas, kappa, pairs_tab, aux_tab, dbar_tab, theta_tab, eta);
+        aggregate_body<QUANT, UPDATE, true>(acc, chunks, n_replicas, kappa, pairs_tab, aux_tab, dbar_tab, theta_tab, eta,
+                                            n_reset, n_tensors, reset_tab);
     else
         aggregate_body<QUANT, UPDATE, false>(acc, chunks, n_replicas, kappa, pairs_tab, aux_tab, dbar_tab, theta_tab,
-                                             eta);
+                                             eta, n_reset, n_tensors, reset_tab);
 }
 
 // Line 5, second half: theta = fl(theta - fl(eta * delta_bar)).
@@ -891,11 +904,11 @@ void launch_compress_batch(const sparseloco_plan* plan, int n_replicas, const fl
 
 template <int QUANT, int UPDATE>
 void launch_aggregate(const sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
-                      const float* const* aux, float* const* dbar, float* const* theta, float eta,
-                      hipStream_t stream) {
+                      const float* const* aux, float* const* dbar, float* const* theta, float eta, int n_reset,
+                      float* const* reset, hipStream_t stream) {
     hipLaunchKernelGGL((aggregate_kernel<QUANT, UPDATE>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
                        plan->d_chunks, gen_entries(plan, false), n_replicas, (uint32_t)plan->kappa, pairs, aux, dbar,
-                       theta, eta);
+                       theta, eta, n_reset, (uint32_t)plan->n_tensors, reset);
 }
 
 }  // namespace
@@ -990,10 +1003,12 @@ static int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows,
     }
     int rc = SPLC_OK;
     // largest pointer table of any call: aggregate (2 per replica + 2 per tensor), compress (3 per
-    // tensor), compress_batch ((1 + 2 R) per tensor + 2 R)
+    // tensor), compress_batch ((1 + 2 R) per tensor + 2 R), aggregate_update with resets
     size_t n_ptrs = 3 * (size_t)n_tensors + 2 * (size_t)kMaxReplicas;
     const size_t n_batch = (1 + 2 * (size_t)kMaxBatch) * (size_t)n_tensors + 2 * (size_t)kMaxBatch;
     if (n_batch > n_ptrs) n_ptrs = n_batch;
+    const size_t n_reset = 2 * (size_t)kMaxReplicas + (2 + (size_t)kMaxBatch) * (size_t)n_tensors;
+    if (n_reset > n_ptrs) n_ptrs = n_reset;
     plan->slot_bytes = (n_ptrs * sizeof(void*) + 255) & ~(size_t)255;
     if (n_chunks > 0 &&
         hipMalloc(reinterpret_cast<void**>(&plan->d_chunks), (size_t)n_chunks * sizeof(ChunkDesc)) != hipSuccess)
@@ -1176,9 +1191,19 @@ int sparseloco_compress_batch(sparseloco_plan* plan, int n_replicas, const float
 
 static int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
                           const float* const* aux, float* const* delta_bar_out, float* const* theta_outer,
-                          float outer_lr, bool update, void* stream) {
+                          float outer_lr, bool update, int n_reset, float* const* const* theta_local_reset,
+                          void* stream) {
     if (!plan || !pairs || !aux) return SPLC_EINVAL;
     if (update ? !theta_outer : !delta_bar_out) return SPLC_EINVAL;
+    if (n_reset < 0 || n_reset > kMaxBatch || (n_reset > 0 && !theta_local_reset)) return SPLC_EINVAL;
+    for (int r = 0; r < n_reset; ++r) {
+        if (!theta_local_reset[r]) return SPLC_EINVAL;
+        for (int i = 0; i < plan->n_tensors; ++i) {
+            if (plan->numel[i] == 0) continue;
+            if (!theta_local_reset[r][i]) return SPLC_EINVAL;
+            if (!aligned(theta_local_reset[r][i], 4)) return SPLC_EALIGN;
+        }
+    }
     if (n_replicas < 1 || n_replicas > kMaxReplicas) return SPLC_EINVAL;
     if (!(outer_lr == outer_lr) || outer_lr - outer_lr != 0.f) return SPLC_EINVAL;
     for (int r = 0; r < n_replicas; ++r) {
@@ -1214,31 +1239,42 @@ static int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t*
         tab[2 * nr + i] = delta_bar_out ? delta_bar_out[i] : nullptr;
         tab[2 * nr + nt + i] = update ? theta_outer[i] : nullptr;
     }
+    for (size_t r = 0; r < (size_t)n_reset; ++r)
+        for (size_t i = 0; i < nt; ++i) tab[2 * nr + 2 * nt + r * nt + i] = theta_local_reset[r][i];
     char* dtab;
-    if ((rc = slot_upload(plan, slot, (2 * nr + 2 * nt) * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
+    if ((rc = slot_upload(plan, slot, (2 * nr + 2 * nt + (size_t)n_reset * nt) * sizeof(void*), st, &dtab)) !=
+        SPLC_OK)
+        return rc;
+    float* const* dreset = reinterpret_cast<float* const*>(dtab + (2 * nr + 2 * nt) * sizeof(void*));
     const uint16_t* const* dp = reinterpret_cast<const uint16_t* const*>(dtab);
     const float* const* dx = reinterpret_cast<const float* const*>(dtab + nr * sizeof(void*));
     float* const* dout =
         delta_bar_out ? reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*)) : nullptr;
     float* const* dth = reinterpret_cast<float* const*>(dtab + (2 * nr + nt) * sizeof(void*));
     const bool q2 = plan->quant == SPLC_QUANT_2BIT;
-    if (q2 && !update) launch_aggregate<SPLC_QUANT_2BIT, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
-    else if (q2) launch_aggregate<SPLC_QUANT_2BIT, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
-    else if (!update) launch_aggregate<SPLC_QUANT_NONE, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
-    else launch_aggregate<SPLC_QUANT_NONE, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, st);
+    if (q2 && !update)
+        launch_aggregate<SPLC_QUANT_2BIT, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
+    else if (q2)
+        launch_aggregate<SPLC_QUANT_2BIT, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
+    else if (!update)
+        launch_aggregate<SPLC_QUANT_NONE, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
+    else
+        launch_aggregate<SPLC_QUANT_NONE, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
     if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
     return slot_release(plan, slot, st);
 }
 
 int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
                          const float* const* aux, float* const* delta_bar_out, void* stream) {
-    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, nullptr, 0.f, false, stream);
+    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, nullptr, 0.f, false, 0, nullptr, stream);
 }
 
 int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
                                 const float* const* aux, float* const* theta_outer, float outer_lr,
-                                float* const* delta_bar_out, void* stream) {
-    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, theta_outer, outer_lr, true, stream);
+                                float* const* delta_bar_out, int n_reset, float* const* const* theta_local_reset,
+                                void* stream) {
+    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, theta_outer, outer_lr, true, n_reset,
+                          theta_local_reset, stream);
 }
 
 int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer, const float* const* delta_bar,

@@ -144,6 +144,30 @@ def test_batched_compress_matches_the_oracle(kappa, R, quant, select):
     parity.check(case, kappa, quant=quant, select=select, batch=True, outer_steps=2, what="batched compress")
 
 
+def test_fused_update_resets_the_replicas():
+    """sparseloco_aggregate_update with reset tables: every theta_local becomes the new theta_outer, bit for
+    bit, on flat and tiled layouts, full and edge chunks."""
+    import torch
+    for shapes in (None, TILED_SHAPES):
+        case = gaussian_case(RAGGED, R=3, seed=401, shapes=shapes)
+        want = parity.run_oracle(case, 32, 0.95, 0.8)
+        plan = B.Plan(case.shapes if shapes else case.numels, 32, True, tiled=shapes is not None)
+        th = [parity._dev(x) for x in case.theta_outer]
+        ef = [[parity._dev(x) for x in r] for r in case.ef]
+        tl = [[parity._dev(x) for x in r] for r in case.theta_local]
+        msgs = [plan.message_buffers() for _ in range(case.R)]
+        B.sparseloco_compress_batch(plan, th, tl, ef, [m[0] for m in msgs], [m[1] for m in msgs], 0.95)
+        B.sparseloco_aggregate_update(plan, [m[0] for m in msgs], [m[1] for m in msgs], th, 0.8, reset=tl[:2])
+        torch.cuda.synchronize()
+        for t in range(len(case.numels)):
+            new = parity.to_np(th[t])
+            parity.assert_close_fp32(new, want[0]["theta"][t], "theta[%d]" % t)
+            for r in range(2):
+                assert parity.to_np(tl[r][t]).tobytes() == new.tobytes()
+            assert parity.to_np(tl[2][t]).tobytes() == case.theta_local[2][t].tobytes()      # not in the reset list
+        plan.close()
+
+
 def test_colliding_indices_many_replicas():
     """All replicas send (almost) the same indices: every accumulator entry gets R addends."""
     rng = np.random.default_rng(77)
