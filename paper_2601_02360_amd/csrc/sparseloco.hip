@@ -613,7 +613,7 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDes
 // ascending replica order -- deterministic, no float atomics, no sort.  Messages are fetched in
 // batches of eight replicas so that the global loads of a batch are in flight together.
 template <int QUANT, int KP>
-__device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_t n_c, uint32_t kappa,
+__device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_t kappa,
                                                  uint32_t kappa_c, int n_replicas,
                                                  const uint16_t* const* __restrict__ pairs_tab,
                                                  const float* const* __restrict__ aux_tab, int lane) {
@@ -662,7 +662,7 @@ __device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_
 
 // Any kappa: one replica after the other, no batching (used for kappa > 256).
 template <int QUANT>
-__device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uint32_t n_c, uint32_t kappa,
+__device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uint32_t kappa,
                                                      uint32_t kappa_c, int n_replicas,
                                                      const uint16_t* const* __restrict__ pairs_tab,
                                                      const float* const* __restrict__ aux_tab, int lane) {
@@ -720,10 +720,10 @@ __device__ __forceinline__ void aggregate_body(float* acc, const ChunkDesc* __re
     for (int s = 0; s < 4; ++s) acc4[s * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
     __syncthreads();
     if (wave == 0) {
-        if (kappa_c <= 64) accumulate_chunk<QUANT, 1>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
-        else if (kappa_c <= 128) accumulate_chunk<QUANT, 2>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
-        else if (kappa_c <= 256) accumulate_chunk<QUANT, 4>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
-        else accumulate_chunk_any<QUANT>(acc, c, n_c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        if (kappa_c <= 64) accumulate_chunk<QUANT, 1>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        else if (kappa_c <= 128) accumulate_chunk<QUANT, 2>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        else if (kappa_c <= 256) accumulate_chunk<QUANT, 4>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        else accumulate_chunk_any<QUANT>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
     }
     __syncthreads();
     const float m = (float)n_replicas;
@@ -911,13 +911,85 @@ void launch_aggregate(const sparseloco_plan* plan, int n_replicas, const uint16_
                        theta, eta, n_reset, (uint32_t)plan->n_tensors, reset);
 }
 
-}  // namespace
+// Shared by sparseloco_aggregate and sparseloco_aggregate_update.
+int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
+                          const float* const* aux, float* const* delta_bar_out, float* const* theta_outer,
+                          float outer_lr, bool update, int n_reset, float* const* const* theta_local_reset,
+                          void* stream) {
+    if (!plan || !pairs || !aux) return SPLC_EINVAL;
+    if (update ? !theta_outer : !delta_bar_out) return SPLC_EINVAL;
+    if (n_reset < 0 || n_reset > kMaxBatch || (n_reset > 0 && !theta_local_reset)) return SPLC_EINVAL;
+    for (int r = 0; r < n_reset; ++r) {
+        if (!theta_local_reset[r]) return SPLC_EINVAL;
+        for (int i = 0; i < plan->n_tensors; ++i) {
+            if (plan->numel[i] == 0) continue;
+            if (!theta_local_reset[r][i]) return SPLC_EINVAL;
+            if (!aligned(theta_local_reset[r][i], 4)) return SPLC_EALIGN;
+        }
+    }
+    if (n_replicas < 1 || n_replicas > kMaxReplicas) return SPLC_EINVAL;
+    if (!(outer_lr == outer_lr) || outer_lr - outer_lr != 0.f) return SPLC_EINVAL;
+    for (int r = 0; r < n_replicas; ++r) {
+        if (!pairs[r] || !aux[r]) return SPLC_EINVAL;
+        if (!aligned(pairs[r], 2) || !aligned(aux[r], 4)) return SPLC_EALIGN;
+    }
+    for (int i = 0; i < plan->n_tensors; ++i) {
+        if (plan->numel[i] == 0) continue;
+        if (delta_bar_out) {
+            if (!delta_bar_out[i]) return SPLC_EINVAL;
+            if (!aligned(delta_bar_out[i], 4)) return SPLC_EALIGN;
+        }
+        if (update) {
+            if (!theta_outer[i]) return SPLC_EINVAL;
+            if (!aligned(theta_outer[i], 4)) return SPLC_EALIGN;
+        }
+    }
+    int rc = check_device(plan);
+    if (rc != SPLC_OK) return rc;
+    if (plan->n_chunks == 0) return SPLC_OK;
 
-extern "C" {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int slot;
+    char* h;
+    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
+    const size_t nt = (size_t)plan->n_tensors, nr = (size_t)n_replicas;
+    void** tab = reinterpret_cast<void**>(h);
+    for (size_t r = 0; r < nr; ++r) {
+        tab[r] = const_cast<uint16_t*>(pairs[r]);
+        tab[nr + r] = const_cast<float*>(aux[r]);
+    }
+    for (size_t i = 0; i < nt; ++i) {
+        tab[2 * nr + i] = delta_bar_out ? delta_bar_out[i] : nullptr;
+        tab[2 * nr + nt + i] = update ? theta_outer[i] : nullptr;
+    }
+    for (size_t r = 0; r < (size_t)n_reset; ++r)
+        for (size_t i = 0; i < nt; ++i) tab[2 * nr + 2 * nt + r * nt + i] = theta_local_reset[r][i];
+    char* dtab;
+    if ((rc = slot_upload(plan, slot, (2 * nr + 2 * nt + (size_t)n_reset * nt) * sizeof(void*), st, &dtab)) !=
+        SPLC_OK)
+        return rc;
+    float* const* dreset = reinterpret_cast<float* const*>(dtab + (2 * nr + 2 * nt) * sizeof(void*));
+    const uint16_t* const* dp = reinterpret_cast<const uint16_t* const*>(dtab);
+    const float* const* dx = reinterpret_cast<const float* const*>(dtab + nr * sizeof(void*));
+    float* const* dout =
+        delta_bar_out ? reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*)) : nullptr;
+    float* const* dth = reinterpret_cast<float* const*>(dtab + (2 * nr + nt) * sizeof(void*));
+    const bool q2 = plan->quant == SPLC_QUANT_2BIT;
+    if (q2 && !update)
+        launch_aggregate<SPLC_QUANT_2BIT, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
+    else if (q2)
+        launch_aggregate<SPLC_QUANT_2BIT, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
+    else if (!update)
+        launch_aggregate<SPLC_QUANT_NONE, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
+    else
+        launch_aggregate<SPLC_QUANT_NONE, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
+    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
+    return slot_release(plan, slot, st);
+}
 
 // Chunk table of one tensor.  rows == 1 (or flat layout): runs of 4096 elements; otherwise 64 x 64 tiles
 // numbered row-major.
-static void append_chunks(std::vector<ChunkDesc>& table, uint32_t tensor, int64_t rows, int64_t cols, bool tiled) {
+void append_chunks(std::vector<ChunkDesc>& table, uint32_t tensor, int64_t rows, int64_t cols, bool tiled) {
     if (rows * cols == 0) return;
     if (!tiled || rows == 1) {
         const int64_t numel = rows * cols;
@@ -954,7 +1026,7 @@ static void append_chunks(std::vector<ChunkDesc>& table, uint32_t tensor, int64_
     }
 }
 
-static int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled,
+int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled,
                       int kappa, int quant_mode) {
     if (!out) return SPLC_EINVAL;
     *out = nullptr;
@@ -1033,6 +1105,10 @@ static int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows,
     *out = plan;
     return SPLC_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel, int kappa, int quant_mode) {
     return plan_build(out, n_tensors, nullptr, numel, false, kappa, quant_mode);
@@ -1185,81 +1261,6 @@ int sparseloco_compress_batch(sparseloco_plan* plan, int n_replicas, const float
         launch_compress_batch<SPLC_QUANT_2BIT>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
     else
         launch_compress_batch<SPLC_QUANT_NONE>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
-    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
-    return slot_release(plan, slot, st);
-}
-
-static int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
-                          const float* const* aux, float* const* delta_bar_out, float* const* theta_outer,
-                          float outer_lr, bool update, int n_reset, float* const* const* theta_local_reset,
-                          void* stream) {
-    if (!plan || !pairs || !aux) return SPLC_EINVAL;
-    if (update ? !theta_outer : !delta_bar_out) return SPLC_EINVAL;
-    if (n_reset < 0 || n_reset > kMaxBatch || (n_reset > 0 && !theta_local_reset)) return SPLC_EINVAL;
-    for (int r = 0; r < n_reset; ++r) {
-        if (!theta_local_reset[r]) return SPLC_EINVAL;
-        for (int i = 0; i < plan->n_tensors; ++i) {
-            if (plan->numel[i] == 0) continue;
-            if (!theta_local_reset[r][i]) return SPLC_EINVAL;
-            if (!aligned(theta_local_reset[r][i], 4)) return SPLC_EALIGN;
-        }
-    }
-    if (n_replicas < 1 || n_replicas > kMaxReplicas) return SPLC_EINVAL;
-    if (!(outer_lr == outer_lr) || outer_lr - outer_lr != 0.f) return SPLC_EINVAL;
-    for (int r = 0; r < n_replicas; ++r) {
-        if (!pairs[r] || !aux[r]) return SPLC_EINVAL;
-        if (!aligned(pairs[r], 2) || !aligned(aux[r], 4)) return SPLC_EALIGN;
-    }
-    for (int i = 0; i < plan->n_tensors; ++i) {
-        if (plan->numel[i] == 0) continue;
-        if (delta_bar_out) {
-            if (!delta_bar_out[i]) return SPLC_EINVAL;
-            if (!aligned(delta_bar_out[i], 4)) return SPLC_EALIGN;
-        }
-        if (update) {
-            if (!theta_outer[i]) return SPLC_EINVAL;
-            if (!aligned(theta_outer[i], 4)) return SPLC_EALIGN;
-        }
-    }
-    int rc = check_device(plan);
-    if (rc != SPLC_OK) return rc;
-    if (plan->n_chunks == 0) return SPLC_OK;
-
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    int slot;
-    char* h;
-    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
-    const size_t nt = (size_t)plan->n_tensors, nr = (size_t)n_replicas;
-    void** tab = reinterpret_cast<void**>(h);
-    for (size_t r = 0; r < nr; ++r) {
-        tab[r] = const_cast<uint16_t*>(pairs[r]);
-        tab[nr + r] = const_cast<float*>(aux[r]);
-    }
-    for (size_t i = 0; i < nt; ++i) {
-        tab[2 * nr + i] = delta_bar_out ? delta_bar_out[i] : nullptr;
-        tab[2 * nr + nt + i] = update ? theta_outer[i] : nullptr;
-    }
-    for (size_t r = 0; r < (size_t)n_reset; ++r)
-        for (size_t i = 0; i < nt; ++i) tab[2 * nr + 2 * nt + r * nt + i] = theta_local_reset[r][i];
-    char* dtab;
-    if ((rc = slot_upload(plan, slot, (2 * nr + 2 * nt + (size_t)n_reset * nt) * sizeof(void*), st, &dtab)) !=
-        SPLC_OK)
-        return rc;
-    float* const* dreset = reinterpret_cast<float* const*>(dtab + (2 * nr + 2 * nt) * sizeof(void*));
-    const uint16_t* const* dp = reinterpret_cast<const uint16_t* const*>(dtab);
-    const float* const* dx = reinterpret_cast<const float* const*>(dtab + nr * sizeof(void*));
-    float* const* dout =
-        delta_bar_out ? reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*)) : nullptr;
-    float* const* dth = reinterpret_cast<float* const*>(dtab + (2 * nr + nt) * sizeof(void*));
-    const bool q2 = plan->quant == SPLC_QUANT_2BIT;
-    if (q2 && !update)
-        launch_aggregate<SPLC_QUANT_2BIT, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
-    else if (q2)
-        launch_aggregate<SPLC_QUANT_2BIT, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
-    else if (!update)
-        launch_aggregate<SPLC_QUANT_NONE, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
-    else
-        launch_aggregate<SPLC_QUANT_NONE, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
     if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
     return slot_release(plan, slot, st);
 }
