@@ -190,6 +190,24 @@ int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas,
                                 float* const* delta_bar_out,
                                 int n_reset, float* const* const* theta_local_reset, void* stream);
 
+/*
+ * Section 2.4 ("Token Embeddings and Heterogeneous Setting"): after every outer
+ * synchronisation the embedding component T_S is projected back onto the
+ * compression subspace S = Col(U) and the part the projection removes is
+ * accumulated into T_perp, so that T_S + T_perp is unchanged:
+ *     T_perp <- T_perp + (T_S - Pi_S(T_S)),  T_S <- Pi_S(T_S),  Pi_S(X) = X U U^T.
+ * With T_perp = 0 on entry this is also the initialisation before training.
+ *   t_s, t_perp: [vocab, d] row-major fp32 device arrays, updated in place.
+ *   u: [d, k] row-major fp32, orthonormal columns (not checked), 1 <= k <= d.
+ *   coeff_ws: device workspace of vocab * k floats owned by the caller; on return
+ *   (after the stream reaches this point) it holds T_S U.
+ * fp32 inputs, fp32 matrix-core arithmetic with fp32 accumulation; the result
+ * differs from exact arithmetic by the usual dot-product rounding of length d
+ * and k.  Pointers 4-byte aligned; vocab < 2^31 - 128.
+ */
+int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, float* coeff_ws,
+                                   int64_t vocab, int d, int k, void* stream);
+
 const char* sparseloco_strerror(int status);
 
 #ifdef __cplusplus

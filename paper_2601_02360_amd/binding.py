@@ -30,7 +30,7 @@ EXPORTS = [
     "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
     "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
     "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
-    "sparseloco_strerror",
+    "sparseloco_reproject_embedding", "sparseloco_strerror",
 ]
 
 _lib = None
@@ -79,6 +79,8 @@ def lib():
         L.sparseloco_aggregate_update.argtypes = [vp, i32, pp, pp, pp, f32, pp, i32, ctypes.POINTER(pp), vp]
         L.sparseloco_compress_batch.restype = i32
         L.sparseloco_compress_batch.argtypes = [vp, i32, pp, ctypes.POINTER(pp), ctypes.POINTER(pp), f32, pp, pp, vp]
+        L.sparseloco_reproject_embedding.restype = i32
+        L.sparseloco_reproject_embedding.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp]
         L.sparseloco_strerror.restype = ctypes.c_char_p
         L.sparseloco_strerror.argtypes = [i32]
         _lib = L
@@ -248,3 +250,17 @@ def sparseloco_compress_batch(plan: Plan, theta_outer, theta_local, ef, pairs_ou
                                          _table(pairs_out), _table(aux_out), _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_compress_batch")
+
+
+def sparseloco_reproject_embedding(t_s: torch.Tensor, t_perp: torch.Tensor, u: torch.Tensor,
+                                   coeff_ws: torch.Tensor, *, stream=None) -> None:
+    """T_perp += T_S - T_S U U^T; T_S = T_S U U^T (in place).  t_s, t_perp: [vocab, d]; u: [d, k];
+    coeff_ws: at least vocab * k floats."""
+    vocab, d = t_s.shape
+    k = u.shape[1]
+    assert t_perp.shape == t_s.shape and u.shape[0] == d and coeff_ws.numel() >= vocab * k
+    assert all(x.dtype == torch.float32 and x.is_contiguous() for x in (t_s, t_perp, u, coeff_ws))
+    rc = lib().sparseloco_reproject_embedding(t_s.data_ptr(), t_perp.data_ptr(), u.data_ptr(), coeff_ws.data_ptr(),
+                                              int(vocab), int(d), int(k), _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_reproject_embedding")

@@ -14,7 +14,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "sparseloco.hip")
+SOURCES = [os.path.join(HERE, "csrc", "sparseloco.hip"), os.path.join(HERE, "csrc", "subspace.hip")]
 LIB = os.path.join(HERE, "libsparseloco.so")
 
 HIPCC_FLAGS = [
@@ -29,7 +29,7 @@ HIPCC_FLAGS = [
 def build(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc, *HIPCC_FLAGS, *extra, SRC, "-o", tmp]
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, *SOURCES, "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

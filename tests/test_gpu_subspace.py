@@ -1,0 +1,81 @@
+"""GPU parity of the embedding re-projection (paper section 2.4) against the float64 oracle.
+
+Tolerance, derived from the arithmetic: the GPU forms two fp32 dot products per output (length d,
+then length k) with fp32 accumulation in an unspecified order.  With rounding errors of the partial
+sums modelled as independent, a dot product of length n has relative error about sqrt(n) * eps
+(eps = 2^-24) with respect to |x| |u|; the bar below is 8 (sqrt(d) + sqrt(k)) eps per ROW in the
+2-norm, relative to the row norm of T_S, for the projection, and the same plus one rounding of the
+sum for T_perp.  The worst-case bound (d + k) eps is also asserted element-wise.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import subspace
+from paper_2601_02360_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+EPS = 2.0 ** -24
+
+
+def run_case(vocab, d, k, seed):
+    rng = np.random.default_rng(seed)
+    u64 = subspace.orthonormal_basis(d, k, seed)
+    u = u64.astype(np.float32)
+    ts = (rng.standard_normal((vocab, d)) * 0.02).astype(np.float32)
+    tp = (rng.standard_normal((vocab, d)) * 0.02).astype(np.float32)
+    want_ts, want_tp = subspace.reproject(ts, tp, u)             # the oracle sees the same fp32 inputs
+    g_ts, g_tp, g_u = (torch.from_numpy(x.copy()).cuda() for x in (ts, tp, u))
+    ws = torch.full((max(vocab * k, 1),), float("nan"), device="cuda")
+    B.sparseloco_reproject_embedding(g_ts, g_tp, g_u, ws)
+    torch.cuda.synchronize()
+    got_ts, got_tp = g_ts.cpu().numpy().astype(np.float64), g_tp.cpu().numpy().astype(np.float64)
+    row = np.linalg.norm(ts.astype(np.float64), axis=1)
+    tol_row = 8 * (np.sqrt(d) + np.sqrt(k)) * EPS * row + 1e-30
+    assert np.all(np.linalg.norm(got_ts - want_ts, axis=1) <= tol_row), "projection"
+    assert np.all(np.linalg.norm(got_tp - want_tp, axis=1) <= tol_row + 4 * EPS * np.linalg.norm(want_tp, axis=1)), "T_perp"
+    worst = (d + k + 4) * EPS * row[:, None] * 1.0 + 4 * EPS * np.abs(want_tp)
+    assert np.all(np.abs(got_ts - want_ts) <= worst) and np.all(np.abs(got_tp - want_tp) <= worst)
+    # the identities of the section hold on the GPU result as well
+    assert np.all(np.linalg.norm((got_ts + got_tp) - (ts.astype(np.float64) + tp), axis=1) <= tol_row)
+    resid = np.linalg.norm(got_ts - (got_ts @ u64) @ u64.T, axis=1)
+    assert np.all(resid <= tol_row)
+    coeff = ws[:vocab * k].cpu().numpy().reshape(vocab, k).astype(np.float64)
+    assert np.all(np.linalg.norm(coeff - ts.astype(np.float64) @ u.astype(np.float64), axis=1) <= tol_row)
+
+
+@pytest.mark.parametrize("vocab,d,k", [(128, 128, 128), (256, 256, 32), (300, 200, 7), (1, 64, 2), (129, 130, 131),
+                                       (1000, 768, 96), (517, 1536, 2), (64, 2048, 256), (2000, 1024, 128)])
+def test_reproject_matches_the_oracle(vocab, d, k):
+    if k > d:
+        k = d
+    run_case(vocab, d, k, seed=vocab + d + k)
+
+
+def test_coordinate_subspace_is_exact():
+    """U = columns of the identity: every product is x * 1 or x * 0, so the result is exact."""
+    vocab, d, k = 200, 192, 64
+    rng = np.random.default_rng(5)
+    cols = rng.permutation(d)[:k]
+    u = np.zeros((d, k), np.float32)
+    u[cols, np.arange(k)] = 1.0
+    ts = rng.standard_normal((vocab, d)).astype(np.float32)
+    tp = rng.standard_normal((vocab, d)).astype(np.float32)
+    g_ts, g_tp, g_u = (torch.from_numpy(x.copy()).cuda() for x in (ts, tp, u))
+    ws = torch.empty(vocab * k, device="cuda")
+    B.sparseloco_reproject_embedding(g_ts, g_tp, g_u, ws)
+    keep = np.zeros(d, bool)
+    keep[cols] = True
+    out_ts, out_tp = g_ts.cpu().numpy(), g_tp.cpu().numpy()
+    assert np.array_equal(out_ts[:, keep], ts[:, keep]) and not out_ts[:, ~keep].any()
+    assert np.array_equal(out_tp[:, ~keep], tp[:, ~keep] + ts[:, ~keep])
+    assert np.array_equal(out_tp[:, keep], tp[:, keep])
+
+
+def test_argument_checks():
+    t = torch.zeros(4, 8, device="cuda")
+    u = torch.zeros(8, 2, device="cuda")
+    L = B.lib()
+    assert L.sparseloco_reproject_embedding(None, t.data_ptr(), u.data_ptr(), t.data_ptr(), 4, 8, 2, None) == B.SPLC_EINVAL
+    assert L.sparseloco_reproject_embedding(t.data_ptr(), t.data_ptr(), u.data_ptr(), t.data_ptr(), 4, 8, 9, None) == B.SPLC_EINVAL
+    assert L.sparseloco_reproject_embedding(t.data_ptr(), t.data_ptr(), u.data_ptr(), t.data_ptr(), 0, 8, 2, None) == B.SPLC_OK
