@@ -87,8 +87,74 @@ def cpu_baseline(rs, cfg, sample_tensors, quant=True, shapes=None):
                       "of the same workload (its first tensors in list order), %.1f s" % (rs.R, len(numels), n, dt)}
 
 
+MFMA_FP32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+
+
+def bench_reproject(args):
+    """Section 2.4's embedding re-projection at the 1B shape: vocabulary 32000, d 2048, k = d/8."""
+    import numpy as np
+    import torch
+    from paper_2601_02360_amd import binding as B
+    from oracle import subspace
+    torch.cuda.set_device(0)
+    vocab, d, k = args.vocab, args.d_model, args.k
+    g = torch.Generator(device="cuda").manual_seed(7)
+    t_s = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
+    t_perp = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
+    u = torch.from_numpy(subspace.orthonormal_basis(d, k, seed=11).astype(np.float32)).cuda()   # input generation only
+    ws = torch.empty(vocab * k, device="cuda")
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for _ in range(args.warmup):
+        B.sparseloco_reproject_embedding(t_s, t_perp, u, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        B.sparseloco_reproject_embedding(t_s, t_perp, u, ws)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    ms_ev = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+    flops = 4.0 * vocab * d * k
+    bytes_ = 4.0 * (vocab * d * 5 + 2 * vocab * k + 2 * d * k)       # T_S read twice + written, T_perp read + written, coefficients
+    result = {
+        "metric": "embedding re-projection rows/sec (section 2.4: T_S <- Pi_S(T_S), T_perp += T_S - Pi_S(T_S))",
+        "value": vocab / (ms * 1e-3), "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "embedding table %d x %d, subspace dimension k = %d (fp32, random orthonormal basis)"
+                               % (vocab, d, k), "algorithmic_flops": flops, "algorithmic_bytes": bytes_,
+                   "hbm_gbs": bytes_ / (ms_ev * 1e-3) / 1e9},
+        "roofline": {"bound": "mfma", "kernel": "gemm_f32_kernel (both passes)", "achieved": flops / (ms_ev * 1e-3) / 1e12,
+                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / (ms_ev * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu:
+        rows = min(vocab, 8192)
+        a, b = t_s[:rows].cpu().numpy(), t_perp[:rows].cpu().numpy()
+        un = u.cpu().numpy()
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            subspace.reproject(a, b, un)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        result["cpu_baseline"] = {"value": rows / dt, "unit": "rows/s", "cores": os.cpu_count(), "kind": "oracle",
+                                  "sample": "float64 numpy oracle on the first %d rows, %d repetitions" % (rows, reps)}
+    print("reproject %d x %d, k=%d: %.3f ms (events %.3f ms) = %.1f TFLOP/s fp32 = %.1f %% of the MFMA peak; %.0f GB/s"
+          % (vocab, d, k, ms, ms_ev, flops / (ms_ev * 1e-3) / 1e12,
+             100 * flops / (ms_ev * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, bytes_ / (ms_ev * 1e-3) / 1e9),
+          file=sys.stderr, flush=True)
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--op", choices=["outer_step", "reproject"], default="outer_step",
+                    help="outer_step (default, the headline); reproject: section 2.4's embedding re-projection")
+    ap.add_argument("--vocab", type=int, default=32000)
+    ap.add_argument("--d-model", type=int, default=2048)
+    ap.add_argument("--k", type=int, default=256)
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
@@ -115,6 +181,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.op == "reproject":
+        bench_reproject(args)
+        return
     torch.cuda.set_device(0)
     cfg = dict(W.WORKLOADS[args.workload])
     if args.kappa:

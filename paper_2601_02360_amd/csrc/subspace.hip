@@ -39,23 +39,50 @@ __device__ __forceinline__ void load8(const float* __restrict__ base, int64_t ld
     }
 }
 
-// Epilogue of pass 1: store the coefficients.
+__device__ __forceinline__ vfloat4 ldg4(const float* p) { return *(const SPLC_GLOBAL vfloat4*)p; }
+__device__ __forceinline__ void stg4(float* p, vfloat4 v) { *(SPLC_GLOBAL vfloat4*)p = v; }
+
+// Epilogues receive four consecutive columns of one output row (col is a multiple of 4; columns
+// at or beyond n_cols do not exist).
+
+// Pass 1: store the coefficients.
 struct StoreCoeff {
     float* c;
     int64_t ld;
-    __device__ __forceinline__ void operator()(int row, int col, float v) const { c[(int64_t)row * ld + col] = v; }
+    __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
+        float* p = c + (int64_t)row * ld + col;
+        if (col + 4 <= n_cols) {
+            stg4(p, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (col + i < n_cols) p[i] = v[i];
+        }
+    }
 };
 
-// Epilogue of pass 2: v = Pi_S(T_S)[row][col].
+// Pass 2: v = Pi_S(T_S)[row][col .. col+3].
 struct UpdateEmbedding {
     float* t_s;
     float* t_perp;
     int64_t ld;
-    __device__ __forceinline__ void operator()(int row, int col, float v) const {
+    __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
         const int64_t at = (int64_t)row * ld + col;
-        const float x = t_s[at];
-        t_perp[at] = __fadd_rn(t_perp[at], __fsub_rn(x, v));
-        t_s[at] = v;
+        if (col + 4 <= n_cols) {
+            const vfloat4 x = ldg4(t_s + at), p = ldg4(t_perp + at);
+            vfloat4 q;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) q[i] = __fadd_rn(p[i], __fsub_rn(x[i], v[i]));
+            stg4(t_perp + at, q);
+            stg4(t_s + at, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (col + i < n_cols) {
+                    t_perp[at + i] = __fadd_rn(t_perp[at + i], __fsub_rn(t_s[at + i], v[i]));
+                    t_s[at + i] = v[i];
+                }
+        }
     }
 };
 
@@ -112,32 +139,63 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < n_tiles) fetch((t + 1) * TK);
-        // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32]
+        // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32].
+        // The operands of the next k pair are read from LDS before the four MFMAs of the current pair
+        // are issued, so that the LDS latency hides behind the matrix pipe.
         const int kq = lane >> 5, rc = lane & 31;
+        float fa[2][2], fb[2][2];
+        auto operands = [&](int kk, int st) {
+            fa[st][0] = As[buf][kk + kq][wm * 64 + rc];
+            fa[st][1] = As[buf][kk + kq][wm * 64 + 32 + rc];
+            fb[st][0] = Bs[buf][kk + kq][wn * 64 + rc];
+            fb[st][1] = Bs[buf][kk + kq][wn * 64 + 32 + rc];
+        };
+        operands(0, 0);
 #pragma unroll
-        for (int kk = 0; kk < TK; kk += 2) {
-            const float a0 = As[buf][kk + kq][wm * 64 + rc], a1 = As[buf][kk + kq][wm * 64 + 32 + rc];
-            const float b0 = Bs[buf][kk + kq][wn * 64 + rc], b1 = Bs[buf][kk + kq][wn * 64 + 32 + rc];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        for (int p = 0; p < TK / 2; ++p) {
+            const int st = p & 1;
+            if (p + 1 < TK / 2) operands(2 * (p + 1), st ^ 1);
+            __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the MFMAs below
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][0], fb[st][0], acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][0], fb[st][1], acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][1], fb[st][0], acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][1], fb[st][1], acc[1][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (t + 1 < n_tiles) stash(buf ^ 1);
         __syncthreads();
     }
 
-    // result layout: register v of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
+    // Epilogue through LDS, 32 output rows at a time, so that global memory sees whole rows
+    // (16 bytes per lane, 512 bytes per row) instead of the MFMA result layout, in which register v
+    // of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32].  The slab reuses the A staging
+    // buffers (same size); the K loop ended with a barrier, so they are free.
+    float* slab = &As[0][0][0];
+    static_assert(2 * TK * PITCH >= 32 * PITCH, "slab must fit the A staging buffers");
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int s = 0; s < 4; ++s) {
+        if (wm == (s >> 1)) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-                if (row < M && col < N) epi(row, col, acc[i][j][v]);
+                for (int v = 0; v < 16; ++v)
+                    slab[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * PITCH + wn * 64 + j * 32 + (lane & 31)] =
+                        acc[s & 1][j][v];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int f = tid + kThreads * q;
+            const int r = f >> 5, c4 = (f & 31) * 4;
+            const int row = m0 + 32 * s + r, col = n0 + c4;
+            if (row < M && col < N) {
+                const float* src = slab + r * PITCH + c4;
+                vfloat4 v = {src[0], src[1], src[2], src[3]};
+                epi(row, col, v, N);
             }
+        }
+        __syncthreads();
+    }
 }
 
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
