@@ -148,10 +148,81 @@ def bench_reproject(args):
     print(json.dumps(result), flush=True)
 
 
+def bench_project(args):
+    """Section 2.2's stage boundary at the 1B shape: rows = tokens of one micro-batch, d 2048, k = d/8."""
+    import numpy as np
+    import torch
+    from paper_2601_02360_amd import binding as B
+    from oracle import subspace
+    torch.cuda.set_device(0)
+    rows, seq, d, k, vocab = args.tokens, args.seq_len, args.d_model, args.k, args.vocab
+    g = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.randn(rows, d, generator=g, device="cuda")
+    t_perp = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
+    pos = torch.randn(seq, d, generator=g, device="cuda") * 0.02
+    tok = torch.randint(0, vocab, (rows,), generator=g, device="cuda", dtype=torch.int32)
+    u = torch.from_numpy(subspace.orthonormal_basis(d, k, seed=11).astype(np.float32)).cuda()   # input generation only
+    xt = torch.empty(rows, k, device="cuda")
+    xh = torch.empty(rows, d, device="cuda")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+
+    def step(i=None):
+        if i is not None:
+            ev[i][0].record()
+        B.sparseloco_subspace_project(x, u, xt, t_perp=t_perp, token_ids=tok, pos_embed=pos)
+        if i is not None:
+            ev[i][1].record()
+        B.sparseloco_subspace_reconstruct(xt, u, xh, t_perp=t_perp, token_ids=tok, pos_embed=pos)
+        if i is not None:
+            ev[i][2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    ms_p = sum(e[0].elapsed_time(e[1]) for e in ev) / len(ev)
+    ms_r = sum(e[1].elapsed_time(e[2]) for e in ev) / len(ev)
+    flops = 4.0 * rows * d * k
+    ach = flops / ((ms_p + ms_r) * 1e-3) / 1e12
+    result = {
+        "metric": "stage-boundary tokens/sec (section 2.2: project to the subspace + reconstruct)",
+        "value": rows / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%d tokens (seq_len %d) x d %d, k = %d, T_perp %d x %d gathered by token, positional "
+                               "table %d x %d" % (rows, seq, d, k, vocab, d, seq, d),
+                   "algorithmic_flops": flops, "kernel_ms": {"project": ms_p, "reconstruct": ms_r}},
+        "roofline": {"bound": "mfma", "kernel": "gemm_f32_kernel (project + reconstruct)", "achieved": ach,
+                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_FP32_PEAK_TFLOPS,
+                     "traffic": None},
+    }
+    if not args.no_cpu:
+        n = min(rows, 4096)
+        a, tp, ps, tk, un = (t.cpu().numpy() for t in (x[:n], t_perp, pos, tok[:n], u))
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            subspace.reconstruct(subspace.project(a, un, tp, tk, ps), un, tp, tk, ps)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        result["cpu_baseline"] = {"value": n / dt, "unit": "tokens/s", "cores": os.cpu_count(), "kind": "oracle",
+                                  "sample": "float64 numpy oracle on the first %d tokens, %d repetitions" % (n, reps)}
+    print("project %.3f ms + reconstruct %.3f ms for %d tokens (d %d, k %d): %.1f TFLOP/s fp32 = %.1f %% of the MFMA peak"
+          % (ms_p, ms_r, rows, d, k, ach, 100 * ach / MFMA_FP32_PEAK_TFLOPS), file=sys.stderr, flush=True)
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", choices=["outer_step", "reproject"], default="outer_step",
-                    help="outer_step (default, the headline); reproject: section 2.4's embedding re-projection")
+    ap.add_argument("--op", choices=["outer_step", "reproject", "project"], default="outer_step",
+                    help="outer_step (default, the headline); reproject: section 2.4's embedding re-projection; "
+                         "project: section 2.2's stage boundary (project + reconstruct)")
+    ap.add_argument("--tokens", type=int, default=16384)
+    ap.add_argument("--seq-len", type=int, default=1024)
     ap.add_argument("--vocab", type=int, default=32000)
     ap.add_argument("--d-model", type=int, default=2048)
     ap.add_argument("--k", type=int, default=256)
@@ -183,6 +254,9 @@ def main():
         sys.exit(1)
     if args.op == "reproject":
         bench_reproject(args)
+        return
+    if args.op == "project":
+        bench_project(args)
         return
     torch.cuda.set_device(0)
     cfg = dict(W.WORKLOADS[args.workload])

@@ -208,6 +208,26 @@ int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas,
 int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, float* coeff_ws,
                                    int64_t vocab, int d, int k, void* stream);
 
+/*
+ * Section 2.2 ("Communication-Efficient Pipeline Parallelism"): what a pipeline
+ * stage sends instead of its activations, and how the next stage rebuilds them.
+ *     project      x_tilde = (x - T_perp[token] - PosEmbed[position]) U      [rows, k]
+ *     reconstruct  x_hat   = x_tilde U^T + T_perp[token] + PosEmbed[position]   [rows, d]
+ * rows = batch * seq_len tokens of a [batch, seq_len, d] row-major tensor; the
+ * position of row r is r % seq_len.  t_perp [vocab, d] with token_ids [rows]
+ * (int32, clamped into [0, vocab)) and pos_embed [seq_len, d] are each optional
+ * (NULL): with both NULL, project is the plain product used for the backward
+ * pass, (grad x) U.  u: [d, k] row-major, 1 <= k <= d.  All arrays fp32 device
+ * memory, 4-byte aligned; fp32 matrix-core arithmetic with fp32 accumulation.
+ * The outputs are fully overwritten and must not overlap the inputs.
+ */
+int sparseloco_subspace_project(const float* x, const float* t_perp, const int32_t* token_ids, int vocab,
+                                const float* pos_embed, int seq_len, const float* u, float* x_tilde,
+                                int64_t rows, int d, int k, void* stream);
+int sparseloco_subspace_reconstruct(const float* x_tilde, const float* t_perp, const int32_t* token_ids,
+                                    int vocab, const float* pos_embed, int seq_len, const float* u,
+                                    float* x_hat, int64_t rows, int d, int k, void* stream);
+
 const char* sparseloco_strerror(int status);
 
 #ifdef __cplusplus

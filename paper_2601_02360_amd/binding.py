@@ -30,7 +30,8 @@ EXPORTS = [
     "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
     "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
     "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
-    "sparseloco_reproject_embedding", "sparseloco_strerror",
+    "sparseloco_reproject_embedding", "sparseloco_subspace_project", "sparseloco_subspace_reconstruct",
+    "sparseloco_strerror",
 ]
 
 _lib = None
@@ -81,6 +82,9 @@ def lib():
         L.sparseloco_compress_batch.argtypes = [vp, i32, pp, ctypes.POINTER(pp), ctypes.POINTER(pp), f32, pp, pp, vp]
         L.sparseloco_reproject_embedding.restype = i32
         L.sparseloco_reproject_embedding.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp]
+        for fn in (L.sparseloco_subspace_project, L.sparseloco_subspace_reconstruct):
+            fn.restype = i32
+            fn.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, i64, i32, i32, vp]
         L.sparseloco_strerror.restype = ctypes.c_char_p
         L.sparseloco_strerror.argtypes = [i32]
         _lib = L
@@ -264,3 +268,37 @@ def sparseloco_reproject_embedding(t_s: torch.Tensor, t_perp: torch.Tensor, u: t
                                               int(vocab), int(d), int(k), _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_reproject_embedding")
+
+
+def _opt(t):
+    return None if t is None else t.data_ptr()
+
+
+def sparseloco_subspace_project(x: torch.Tensor, u: torch.Tensor, out: torch.Tensor, *, t_perp=None, token_ids=None,
+                                pos_embed=None, stream=None) -> None:
+    """out[rows, k] = (x - t_perp[token_ids] - pos_embed[row % seq_len]) @ u;  x: [rows, d], u: [d, k]."""
+    rows, d = x.shape
+    k = u.shape[1]
+    assert out.shape == (rows, k) and x.is_contiguous() and u.is_contiguous() and out.is_contiguous()
+    assert token_ids is None or token_ids.dtype == torch.int32
+    rc = lib().sparseloco_subspace_project(x.data_ptr(), _opt(t_perp), _opt(token_ids),
+                                           0 if t_perp is None else t_perp.shape[0], _opt(pos_embed),
+                                           0 if pos_embed is None else pos_embed.shape[0], u.data_ptr(),
+                                           out.data_ptr(), int(rows), int(d), int(k), _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_subspace_project")
+
+
+def sparseloco_subspace_reconstruct(x_tilde: torch.Tensor, u: torch.Tensor, out: torch.Tensor, *, t_perp=None,
+                                    token_ids=None, pos_embed=None, stream=None) -> None:
+    """out[rows, d] = x_tilde @ u.T + t_perp[token_ids] + pos_embed[row % seq_len]."""
+    rows, k = x_tilde.shape
+    d = u.shape[0]
+    assert out.shape == (rows, d) and x_tilde.is_contiguous() and u.is_contiguous() and out.is_contiguous()
+    assert token_ids is None or token_ids.dtype == torch.int32
+    rc = lib().sparseloco_subspace_reconstruct(x_tilde.data_ptr(), _opt(t_perp), _opt(token_ids),
+                                               0 if t_perp is None else t_perp.shape[0], _opt(pos_embed),
+                                               0 if pos_embed is None else pos_embed.shape[0], u.data_ptr(),
+                                               out.data_ptr(), int(rows), int(d), int(k), _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_subspace_reconstruct")

@@ -7,6 +7,11 @@
 // 256-lane workgroup, each wave a 64 x 64 quarter (2 x 2 MFMA tiles).
 //   pass 1:  C = T_S U                       (vocab x k, caller's workspace)
 //   pass 2:  R = C U^T, fused with the update of T_perp and T_S (R is never stored separately)
+//
+// The same GEMM kernel, with a prologue on its A operand or another epilogue, gives the compressed
+// inter-stage traffic of section 2.2:
+//     project      X~ = (X - T_perp[x] - PosEmbed) U        (also  grad_X U  with nothing subtracted)
+//     reconstruct  X^ = X~ U^T + T_perp[x] + PosEmbed
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -86,13 +91,87 @@ struct UpdateEmbedding {
     }
 };
 
+// The high-rank part of an activation row (section 2.2): T_perp[token of the row] + PosEmbed[position of
+// the row]; either table may be absent.  Rows are tokens of a [batch, seq_len, d] tensor, so the position
+// of row r is r % seq_len.  Token ids are clamped into the table.
+struct HighRank {
+    const float* t_perp;     // [vocab, d] or nullptr
+    const int32_t* token;    // [rows] (required with t_perp)
+    int vocab;
+    const float* pos;        // [seq_len, d] or nullptr
+    int seq_len;
+    int64_t ld;              // d
+    __device__ __forceinline__ const float* perp_row(int row) const {
+        int t = token[row];
+        t = t < 0 ? 0 : (t >= vocab ? vocab - 1 : t);
+        return t_perp + (int64_t)t * ld;
+    }
+    __device__ __forceinline__ const float* pos_row(int row) const { return pos + (int64_t)(row % seq_len) * ld; }
+};
+
+// A-operand prologues: called with the eight loaded values of (row, col .. col+7).
+struct NoPrologue {
+    __device__ __forceinline__ void operator()(int, int, int, int, float (&)[8]) const {}
+};
+// v <- fl(fl(v - T_perp[x]) - PosEmbed)
+struct SubtractHighRank {
+    HighRank h;
+    __device__ __forceinline__ void operator()(int row, int col, int rows, int cols, float (&v)[8]) const {
+        if (row >= rows) return;
+        if (h.t_perp) {
+            float t[8];
+            load8(h.perp_row(row), h.ld, 0, col, 1, cols, t);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = __fsub_rn(v[i], t[i]);
+        }
+        if (h.pos) {
+            float t[8];
+            load8(h.pos_row(row), h.ld, 0, col, 1, cols, t);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = __fsub_rn(v[i], t[i]);
+        }
+    }
+};
+
+// Epilogue of reconstruct: out <- fl(fl(v + T_perp[x]) + PosEmbed)
+struct AddHighRank {
+    HighRank h;
+    float* out;
+    __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
+        float* p = out + (int64_t)row * h.ld + col;
+        if (col + 4 <= n_cols) {
+            if (h.t_perp) {
+                const vfloat4 t = ldg4(h.perp_row(row) + col);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], t[i]);
+            }
+            if (h.pos) {
+                const vfloat4 t = ldg4(h.pos_row(row) + col);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], t[i]);
+            }
+            stg4(p, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (col + i < n_cols) {
+                    float r = v[i];
+                    if (h.t_perp) r = __fadd_rn(r, h.perp_row(row)[col + i]);
+                    if (h.pos) r = __fadd_rn(r, h.pos_row(row)[col + i]);
+                    p[i] = r;
+                }
+        }
+    }
+};
+
 // C = A * B for row-major A (M x K, lda).  B_NK = false: B is row-major K x N (ldb).
 // B_NK = true: B is given as its transpose, row-major N x K (ldb), i.e. B[k][n] = Bt[n][k].
-// Every output element goes through epi(row, col, value).
-template <bool B_NK, class Epi>
+// The A values pass through pro(row, col, M, K, values[8]) on their way in; the output goes
+// through epi(row, col, four values, N).
+template <bool B_NK, class Pro, class Epi>
 __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restrict__ A, int64_t lda,
                                                             const float* __restrict__ B, int64_t ldb, int M, int N,
-                                                            int K, Epi epi) {
+                                                            int K, Pro pro, Epi epi) {
     __shared__ float As[2][TK][PITCH];
     __shared__ float Bs[2][TK][PITCH];
     const int tid = threadIdx.x;
@@ -117,6 +196,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
     float ra[8], rb[8];
     auto fetch = [&](int k0) {
         load8(A, lda, m0 + ar, k0 + ak, M, K, ra);
+        pro(m0 + ar, k0 + ak, M, K, ra);
         if (B_NK) load8(B, ldb, n0 + ar, k0 + ak, N, K, rb);
         else load8(B, ldb, k0 + bk, n0 + bn, K, N, rb);
     };
@@ -213,14 +293,65 @@ extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const f
     // pass 1: coeff = T_S U            (M x k) = (M x d)(d x k)
     {
         dim3 grid((unsigned)((k + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
-        hipLaunchKernelGGL((gemm_f32_kernel<false, StoreCoeff>), grid, dim3(kThreads), 0, st, t_s, (int64_t)d, u,
-                           (int64_t)k, M, k, d, StoreCoeff{coeff_ws, (int64_t)k});
+        hipLaunchKernelGGL((gemm_f32_kernel<false, NoPrologue, StoreCoeff>), grid, dim3(kThreads), 0, st, t_s,
+                           (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k});
     }
     // pass 2: Pi = coeff U^T           (M x d) = (M x k)(k x d), U given as d x k = the N x K form
     {
         dim3 grid((unsigned)((d + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
-        hipLaunchKernelGGL((gemm_f32_kernel<true, UpdateEmbedding>), grid, dim3(kThreads), 0, st, coeff_ws,
-                           (int64_t)k, u, (int64_t)k, M, d, k, UpdateEmbedding{t_s, t_perp, (int64_t)d});
+        hipLaunchKernelGGL((gemm_f32_kernel<true, NoPrologue, UpdateEmbedding>), grid, dim3(kThreads), 0, st,
+                           coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{},
+                           UpdateEmbedding{t_s, t_perp, (int64_t)d});
     }
+    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
+}
+
+namespace {
+int check_high_rank(const float* t_perp, const int32_t* token_ids, int vocab, const float* pos_embed, int seq_len) {
+    if (t_perp && (!token_ids || vocab < 1)) return SPLC_EINVAL;
+    if (pos_embed && seq_len < 1) return SPLC_EINVAL;
+    if ((t_perp && !aligned4(t_perp)) || (token_ids && !aligned4(token_ids)) || (pos_embed && !aligned4(pos_embed)))
+        return SPLC_EALIGN;
+    return SPLC_OK;
+}
+}  // namespace
+
+extern "C" int sparseloco_subspace_project(const float* x, const float* t_perp, const int32_t* token_ids, int vocab,
+                                           const float* pos_embed, int seq_len, const float* u, float* x_tilde,
+                                           int64_t rows, int d, int k, void* stream) {
+    if (!x || !u || !x_tilde) return SPLC_EINVAL;
+    if (rows < 0 || rows > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d) return SPLC_EINVAL;
+    int rc = check_high_rank(t_perp, token_ids, vocab, pos_embed, seq_len);
+    if (rc != SPLC_OK) return rc;
+    if (!aligned4(x) || !aligned4(u) || !aligned4(x_tilde)) return SPLC_EALIGN;
+    if (rows == 0) return SPLC_OK;
+    const int M = (int)rows;
+    const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
+    dim3 grid((unsigned)((k + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (t_perp || pos_embed)
+        hipLaunchKernelGGL((gemm_f32_kernel<false, SubtractHighRank, StoreCoeff>), grid, dim3(kThreads), 0, st, x,
+                           (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank{h}, StoreCoeff{x_tilde, (int64_t)k});
+    else
+        hipLaunchKernelGGL((gemm_f32_kernel<false, NoPrologue, StoreCoeff>), grid, dim3(kThreads), 0, st, x,
+                           (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{x_tilde, (int64_t)k});
+    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
+}
+
+extern "C" int sparseloco_subspace_reconstruct(const float* x_tilde, const float* t_perp, const int32_t* token_ids,
+                                               int vocab, const float* pos_embed, int seq_len, const float* u,
+                                               float* x_hat, int64_t rows, int d, int k, void* stream) {
+    if (!x_tilde || !u || !x_hat) return SPLC_EINVAL;
+    if (rows < 0 || rows > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d) return SPLC_EINVAL;
+    int rc = check_high_rank(t_perp, token_ids, vocab, pos_embed, seq_len);
+    if (rc != SPLC_OK) return rc;
+    if (!aligned4(x_tilde) || !aligned4(u) || !aligned4(x_hat)) return SPLC_EALIGN;
+    if (rows == 0) return SPLC_OK;
+    const int M = (int)rows;
+    const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
+    dim3 grid((unsigned)((d + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL((gemm_f32_kernel<true, NoPrologue, AddHighRank>), grid, dim3(kThreads), 0, st, x_tilde,
+                       (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat});
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }

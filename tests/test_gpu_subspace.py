@@ -79,3 +79,32 @@ def test_argument_checks():
     assert L.sparseloco_reproject_embedding(None, t.data_ptr(), u.data_ptr(), t.data_ptr(), 4, 8, 2, None) == B.SPLC_EINVAL
     assert L.sparseloco_reproject_embedding(t.data_ptr(), t.data_ptr(), u.data_ptr(), t.data_ptr(), 4, 8, 9, None) == B.SPLC_EINVAL
     assert L.sparseloco_reproject_embedding(t.data_ptr(), t.data_ptr(), u.data_ptr(), t.data_ptr(), 0, 8, 2, None) == B.SPLC_OK
+
+
+@pytest.mark.parametrize("rows,seq,d,k,vocab,use_perp,use_pos", [
+    (256, 64, 128, 16, 50, True, True), (300, 100, 200, 7, 33, True, True), (129, 43, 130, 130, 5, True, False),
+    (512, 128, 768, 96, 1000, False, True), (1000, 250, 1536, 2, 64, True, True), (640, 64, 2048, 256, 512, False, False)])
+def test_project_and_reconstruct_match_the_oracle(rows, seq, d, k, vocab, use_perp, use_pos):
+    rng = np.random.default_rng(rows + d + k)
+    u64 = subspace.orthonormal_basis(d, k, rows)
+    u = u64.astype(np.float32)
+    x = rng.standard_normal((rows, d)).astype(np.float32)
+    tp = (rng.standard_normal((vocab, d)) * 0.5).astype(np.float32) if use_perp else None
+    tok = rng.integers(0, vocab, rows).astype(np.int32) if use_perp else None
+    pos = (rng.standard_normal((seq, d)) * 0.5).astype(np.float32) if use_pos else None
+    dev = lambda a: None if a is None else torch.from_numpy(a.copy()).cuda()
+    g_x, g_u, g_tp, g_tok, g_pos = dev(x), dev(u), dev(tp), dev(tok), dev(pos)
+    out_t = torch.full((rows, k), float("nan"), device="cuda")
+    B.sparseloco_subspace_project(g_x, g_u, out_t, t_perp=g_tp, token_ids=g_tok, pos_embed=g_pos)
+    want_t = subspace.project(x, u, tp, tok, pos)
+    high = np.zeros((rows, d)) if (tp is None and pos is None) else subspace.reconstruct(np.zeros((rows, k)), u, tp, tok, pos)
+    scale = np.linalg.norm(x.astype(np.float64), axis=1) + np.linalg.norm(high, axis=1)
+    tol = 8 * (np.sqrt(d) + np.sqrt(k)) * EPS * scale
+    got_t = out_t.cpu().numpy().astype(np.float64)
+    assert np.all(np.linalg.norm(got_t - want_t, axis=1) <= tol), "project"
+    # reconstruct from the GPU's own x_tilde, compared with the oracle applied to the same x_tilde
+    out_h = torch.full((rows, d), float("nan"), device="cuda")
+    B.sparseloco_subspace_reconstruct(out_t, g_u, out_h, t_perp=g_tp, token_ids=g_tok, pos_embed=g_pos)
+    want_h = subspace.reconstruct(out_t.cpu().numpy(), u, tp, tok, pos)
+    got_h = out_h.cpu().numpy().astype(np.float64)
+    assert np.all(np.linalg.norm(got_h - want_h, axis=1) <= tol), "reconstruct"

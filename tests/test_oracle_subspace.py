@@ -48,3 +48,30 @@ def test_identities_of_section_2_4():
     full = subspace.orthonormal_basis(d, d, seed=4)
     f_ts, f_tp = subspace.reproject(ts, tp, full)
     assert np.allclose(f_ts, ts, atol=1e-12) and np.allclose(f_tp, tp, atol=1e-12)
+
+
+def test_projection_of_activations_closed_forms():
+    """Section 2.2: activations whose low-rank part lies in Col(U) survive project -> reconstruct unchanged;
+    with a coordinate subspace the transmitted values are the selected columns of x minus the high-rank part."""
+    rng = np.random.default_rng(2)
+    rows, d, k, vocab, seq = 12, 10, 3, 7, 4
+    tp, pos = rng.standard_normal((vocab, d)), rng.standard_normal((seq, d))
+    tok = rng.integers(0, vocab, rows)
+    u = np.zeros((d, k))
+    cols = [7, 2, 5]
+    u[cols, np.arange(k)] = 1.0
+    x = rng.standard_normal((rows, d))
+    xt = subspace.project(x, u, tp, tok, pos)
+    high = tp[tok] + pos[np.arange(rows) % seq]
+    assert np.allclose(xt, (x - high)[:, cols], rtol=0, atol=1e-15)
+    xh = subspace.reconstruct(xt, u, tp, tok, pos)
+    assert np.allclose(xh[:, cols], x[:, cols], atol=1e-14)
+    rest = np.setdiff1d(np.arange(d), cols)
+    assert np.allclose(xh[:, rest], high[:, rest], atol=1e-15)
+    # lossless when the residual activations live in the subspace
+    q = subspace.orthonormal_basis(d, k, seed=9)
+    x_in = rng.standard_normal((rows, k)) @ q.T + high
+    assert np.allclose(subspace.reconstruct(subspace.project(x_in, q, tp, tok, pos), q, tp, tok, pos), x_in, atol=1e-13)
+    # backward: plain product
+    g = rng.standard_normal((rows, d))
+    assert np.allclose(subspace.project(g, u), g[:, cols], rtol=0, atol=0)
