@@ -111,24 +111,45 @@ struct HighRank {
 
 // A-operand prologues: called with the eight loaded values of (row, col .. col+7).
 struct NoPrologue {
+    __device__ __forceinline__ void prepare(int, int) {}
     __device__ __forceinline__ void operator()(int, int, int, int, float (&)[8]) const {}
+    __device__ __forceinline__ void four(int, int, int, int, float (&)[8]) const {}
 };
 // v <- fl(fl(v - T_perp[x]) - PosEmbed)
 struct SubtractHighRank {
     HighRank h;
+    const float* tabs[2];        // this lane's T_perp row and positional row (one matrix row per lane)
+    // Called once per lane with the matrix row it stages: the token lookup leaves the K loop.
+    __device__ __forceinline__ void prepare(int row, int rows) {
+        tabs[0] = (h.t_perp && row < rows) ? h.perp_row(row) : nullptr;
+        tabs[1] = (h.pos && row < rows) ? h.pos_row(row) : nullptr;
+    }
     __device__ __forceinline__ void operator()(int row, int col, int rows, int cols, float (&v)[8]) const {
         if (row >= rows) return;
-        if (h.t_perp) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (!tabs[k]) continue;
             float t[8];
-            load8(h.perp_row(row), h.ld, 0, col, 1, cols, t);
+            load8(tabs[k], h.ld, 0, col, 1, cols, t);
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[i] = __fsub_rn(v[i], t[i]);
         }
-        if (h.pos) {
-            float t[8];
-            load8(h.pos_row(row), h.ld, 0, col, 1, cols, t);
+    }
+    // the same for the first four values only (columns col .. col+3)
+    __device__ __forceinline__ void four(int row, int col, int rows, int cols, float (&v)[8]) const {
+        if (row >= rows) return;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = __fsub_rn(v[i], t[i]);
+        for (int k = 0; k < 2; ++k) {
+            if (!tabs[k]) continue;
+            if (col + 4 <= cols) {
+                const vfloat4 t = ldg4(tabs[k] + col);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = __fsub_rn(v[i], t[i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (col + i < cols) v[i] = __fsub_rn(v[i], tabs[k][col + i]);
+            }
         }
     }
 };
@@ -168,65 +189,91 @@ struct AddHighRank {
 // B_NK = true: B is given as its transpose, row-major N x K (ldb), i.e. B[k][n] = Bt[n][k].
 // The A values pass through pro(row, col, M, K, values[8]) on their way in; the output goes
 // through epi(row, col, four values, N).
-template <bool B_NK, class Pro, class Epi>
+template <int TM_, bool B_NK, class Pro, class Epi>
 __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restrict__ A, int64_t lda,
                                                             const float* __restrict__ B, int64_t ldb, int M, int N,
                                                             int K, Pro pro, Epi epi) {
+    // TM_ x 128 output tile; the four waves form a 2 x 2 grid, each with MI x 2 MFMA tiles of 32 x 32
+    // (MI = 2 for TM_ = 128, MI = 1 for TM_ = 64, which gives small problems twice the workgroups).
+    static_assert(TM_ == 128 || TM_ == 64, "supported M tiles");
+    constexpr int MI = TM_ / 64;
+    constexpr int AF = TM_ / 16;             // floats of the A tile per lane: 8 or 4
     __shared__ float As[2][TK][PITCH];
     __shared__ float Bs[2][TK][PITCH];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
-    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int m0 = blockIdx.y * TM_, n0 = blockIdx.x * TN;
 
-    v16f acc[2][2];
+    v16f acc[MI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Staging assignment.  "Row-of-k" tiles (A always, B when given as N x K): lane t takes matrix
-    // row t / 2 and eight consecutive k.  "k-major" tiles (B as K x N): lane t takes k = t / 16 and
-    // eight consecutive n.
-    const int ar = tid >> 1, ak = (tid & 1) * 8;
+    // Staging assignment.  "Row-of-k" tiles (A always, B when given as N x K): lane t takes one matrix
+    // row and AF (A) or eight (B) consecutive k.  "k-major" tiles (B as K x N): lane t takes
+    // k = t / 16 and eight consecutive n.
+    const int ar = tid / (TK / AF), ak = (tid % (TK / AF)) * AF;
+    const int br = tid >> 1, bkk = (tid & 1) * 8;
     const int bk = tid >> 4, bn = (tid & 15) * 8;
-    float ra[8], rb[8];
-    auto fetch = [&](int k0) {
-        load8(A, lda, m0 + ar, k0 + ak, M, K, ra);
-        pro(m0 + ar, k0 + ak, M, K, ra);
-        if (B_NK) load8(B, ldb, n0 + ar, k0 + ak, N, K, rb);
-        else load8(B, ldb, k0 + bk, n0 + bn, K, N, rb);
-    };
-    auto stash = [&](int buf) {
+    // Global loads run two K tiles ahead of the MFMAs (one tile of matrix work is shorter than the
+    // memory latency): tile t+2 is fetched into registers while tile t is multiplied and tile t+1,
+    // fetched one iteration earlier, waits in a second register set for its turn to go to LDS.
+    float ra[2][8], rb[2][8];
+    auto fetch = [&](int k0, float (&qa)[8], float (&qb)[8]) {
+        if (AF == 8) {
+            load8(A, lda, m0 + ar, k0 + ak, M, K, qa);
+            pro(m0 + ar, k0 + ak, M, K, qa);
+        } else {
+            // half a load8: the upper four values are not used
+            const int row = m0 + ar, col = k0 + ak;
+            if (row < M && col + 4 <= K) {
+                const vfloat4 v = ldg4(A + (int64_t)row * lda + col);
+                qa[0] = v.x; qa[1] = v.y; qa[2] = v.z; qa[3] = v.w;
+            } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) As[buf][ak + i][ar] = ra[i];
+                for (int i = 0; i < 4; ++i)
+                    qa[i] = (row < M && col + i < K) ? A[(int64_t)row * lda + col + i] : 0.f;
+            }
+            qa[4] = qa[5] = qa[6] = qa[7] = 0.f;
+            pro.four(row, col, M, K, qa);
+        }
+        if (B_NK) load8(B, ldb, n0 + br, k0 + bkk, N, K, qb);
+        else load8(B, ldb, k0 + bk, n0 + bn, K, N, qb);
+    };
+    auto stash = [&](int buf, const float (&qa)[8], const float (&qb)[8]) {
+#pragma unroll
+        for (int i = 0; i < AF; ++i) As[buf][ak + i][ar] = qa[i];
         if (B_NK) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) Bs[buf][ak + i][ar] = rb[i];
+            for (int i = 0; i < 8; ++i) Bs[buf][bkk + i][br] = qb[i];
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) Bs[buf][bk][bn + i] = rb[i];
+            for (int i = 0; i < 8; ++i) Bs[buf][bk][bn + i] = qb[i];
         }
     };
 
     const int n_tiles = (K + TK - 1) / TK;
-    fetch(0);
-    stash(0);
+    pro.prepare(m0 + ar, M);
+    fetch(0, ra[0], rb[0]);
+    stash(0, ra[0], rb[0]);
+    if (n_tiles > 1) fetch(TK, ra[0], rb[0]);
     __syncthreads();
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
-        if (t + 1 < n_tiles) fetch((t + 1) * TK);
+        if (t + 2 < n_tiles) fetch((t + 2) * TK, ra[1], rb[1]);
         // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32].
-        // The operands of the next k pair are read from LDS before the four MFMAs of the current pair
-        // are issued, so that the LDS latency hides behind the matrix pipe.
+        // The operands of the next k pair are read from LDS before the MFMAs of the current pair are
+        // issued, so that the LDS latency hides behind the matrix pipe.
         const int kq = lane >> 5, rc = lane & 31;
-        float fa[2][2], fb[2][2];
+        float fa[2][MI], fb[2][2];
         auto operands = [&](int kk, int st) {
-            fa[st][0] = As[buf][kk + kq][wm * 64 + rc];
-            fa[st][1] = As[buf][kk + kq][wm * 64 + 32 + rc];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) fa[st][i] = As[buf][kk + kq][wm * (32 * MI) + 32 * i + rc];
             fb[st][0] = Bs[buf][kk + kq][wn * 64 + rc];
             fb[st][1] = Bs[buf][kk + kq][wn * 64 + 32 + rc];
         };
@@ -236,13 +283,16 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
             const int st = p & 1;
             if (p + 1 < TK / 2) operands(2 * (p + 1), st ^ 1);
             __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the MFMAs below
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][0], fb[st][0], acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][0], fb[st][1], acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][1], fb[st][0], acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][1], fb[st][1], acc[1][1], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][i], fb[st][0], acc[i][0], 0, 0, 0);
+                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][i], fb[st][1], acc[i][1], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (t + 1 < n_tiles) stash(buf ^ 1);
+        if (t + 1 < n_tiles) stash(buf ^ 1, ra[0], rb[0]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { ra[0][i] = ra[1][i]; rb[0][i] = rb[1][i]; }
         __syncthreads();
     }
 
@@ -253,14 +303,14 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
     float* slab = &As[0][0][0];
     static_assert(2 * TK * PITCH >= 32 * PITCH, "slab must fit the A staging buffers");
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        if (wm == (s >> 1)) {
+    for (int s = 0; s < TM_ / 32; ++s) {
+        if (wm == s / MI) {
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
                     slab[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * PITCH + wn * 64 + j * 32 + (lane & 31)] =
-                        acc[s & 1][j][v];
+                        acc[s % MI][j][v];
         }
         __syncthreads();
 #pragma unroll
@@ -278,6 +328,23 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
     }
 }
 
+// Launch with the 128-row tile, or the 64-row tile when that is needed to give every compute unit
+// several workgroups.
+template <bool B_NK, class Pro, class Epi>
+void launch_gemm(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
+                 hipStream_t st) {
+    const int64_t wg128 = (int64_t)((M + 127) / 128) * ((N + TN - 1) / TN);
+    if (wg128 >= 4 * 256) {
+        dim3 grid((unsigned)((N + TN - 1) / TN), (unsigned)((M + 127) / 128));
+        hipLaunchKernelGGL((gemm_f32_kernel<128, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B, ldb, M, N, K,
+                           pro, epi);
+    } else {
+        dim3 grid((unsigned)((N + TN - 1) / TN), (unsigned)((M + 63) / 64));
+        hipLaunchKernelGGL((gemm_f32_kernel<64, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B, ldb, M, N, K,
+                           pro, epi);
+    }
+}
+
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
 
 }  // namespace
@@ -291,18 +358,10 @@ extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const f
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int M = (int)vocab;
     // pass 1: coeff = T_S U            (M x k) = (M x d)(d x k)
-    {
-        dim3 grid((unsigned)((k + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
-        hipLaunchKernelGGL((gemm_f32_kernel<false, NoPrologue, StoreCoeff>), grid, dim3(kThreads), 0, st, t_s,
-                           (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k});
-    }
+    launch_gemm<false>(t_s, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k}, st);
     // pass 2: Pi = coeff U^T           (M x d) = (M x k)(k x d), U given as d x k = the N x K form
-    {
-        dim3 grid((unsigned)((d + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
-        hipLaunchKernelGGL((gemm_f32_kernel<true, NoPrologue, UpdateEmbedding>), grid, dim3(kThreads), 0, st,
-                           coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{},
-                           UpdateEmbedding{t_s, t_perp, (int64_t)d});
-    }
+    launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{},
+                      UpdateEmbedding{t_s, t_perp, (int64_t)d}, st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
@@ -327,14 +386,12 @@ extern "C" int sparseloco_subspace_project(const float* x, const float* t_perp, 
     if (rows == 0) return SPLC_OK;
     const int M = (int)rows;
     const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
-    dim3 grid((unsigned)((k + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (t_perp || pos_embed)
-        hipLaunchKernelGGL((gemm_f32_kernel<false, SubtractHighRank, StoreCoeff>), grid, dim3(kThreads), 0, st, x,
-                           (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank{h}, StoreCoeff{x_tilde, (int64_t)k});
+        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank{h, {nullptr, nullptr}},
+                           StoreCoeff{x_tilde, (int64_t)k}, st);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<false, NoPrologue, StoreCoeff>), grid, dim3(kThreads), 0, st, x,
-                           (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{x_tilde, (int64_t)k});
+        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{x_tilde, (int64_t)k}, st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
@@ -349,9 +406,7 @@ extern "C" int sparseloco_subspace_reconstruct(const float* x_tilde, const float
     if (rows == 0) return SPLC_OK;
     const int M = (int)rows;
     const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
-    dim3 grid((unsigned)((d + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL((gemm_f32_kernel<true, NoPrologue, AddHighRank>), grid, dim3(kThreads), 0, st, x_tilde,
-                       (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat});
+    launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat}, st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
