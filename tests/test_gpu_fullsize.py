@@ -177,3 +177,38 @@ def test_workload2_full_size_tiled_layout():
 def test_workload4_ragged_shapes_tiled_layout():
     """2050 x 5630 and 32001 x 2048 matrices: edge tiles on both sides, odd row starts for the bf16 source."""
     fullsize_check(4, 2, W.WORKLOADS[4]["kappa"], tensors=list(range(9)) + [144, 145], n_random=200, tiled=True)
+
+
+def test_one_tensor_with_more_than_2_31_elements():
+    """64-bit addressing: a single tensor of 2^31 + 10000 elements (byte offsets beyond 2^33), R = 1.
+    The oracle recomputes the chunks around the 2^31-element mark, the first and the last (partial) chunk
+    and random ones."""
+    n = (1 << 31) + 10000
+    g = torch.Generator(device="cuda").manual_seed(5)
+    theta_o = torch.randn(n, generator=g, device="cuda") * 0.02
+    theta_l = theta_o - torch.randn(n, generator=g, device="cuda") * 1e-3
+    ef = torch.randn(n, generator=g, device="cuda") * 1e-4
+    kappa = 32
+    n_chunks = (n + CH - 1) // CH
+    rng = np.random.default_rng(1)
+    mark = (1 << 31) // CH
+    picks = sorted(set([(0, 0), (0, n_chunks - 1), (0, mark - 1), (0, mark), (0, mark + 1), (0, (1 << 30) // CH)] +
+                       [(0, int(c)) for c in rng.integers(0, n_chunks, 60)]))
+    cum = np.array([0, n_chunks])
+    th0, tl0, ef0 = gather([theta_o], picks), gather([theta_l], picks), gather([ef], picks)
+    plan = B.Plan([n], kappa)
+    assert plan.num_chunks == n_chunks and plan.num_params == n
+    msg = plan.message_buffers()
+    dbar = torch.empty(n, device="cuda")
+    B.sparseloco_compress(plan, [ef], msg[0], msg[1], 0.95, theta_outer=[theta_o], theta_local=[theta_l])
+    B.sparseloco_aggregate(plan, [msg[0]], [msg[1]], [dbar])
+    B.sparseloco_outer_update(plan, [theta_o], [dbar], 1.0)
+    torch.cuda.synchronize()
+    all_chunk_properties(plan, msg, [n], kappa)
+    gp, ga = gather_msg(msg, picks, cum, kappa)
+    got = [dict(pairs=[gp], aux=[ga], ef=[gather([ef], picks)], dbar=gather([dbar], picks),
+                theta=gather([theta_o], picks))]
+    plan.close()
+    case = parity.HostCase(th0, [ef0], theta_local=[tl0])
+    want = parity.run_oracle(case, kappa, 0.95, 1.0)
+    parity.compare(got, want, "2^31+ elements")
