@@ -607,23 +607,28 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDes
 }
 
 // Line 5, first half: sum of the decoded messages of one chunk into a dense LDS accumulator.
-// Executed by ONE wave: LDS operations of a wave complete in program order, so the add of
-// replica r+1 at some index sees the add of replica r at the same index without a barrier, and
-// inside one replica the indices are distinct.  Every element therefore receives its addends in
-// ascending replica order -- deterministic, no float atomics, no sort.  Messages are fetched in
-// batches of eight replicas so that the global loads of a batch are in flight together.
+// Replicas are applied in batches of eight; a batch is applied by ONE wave: LDS operations of a
+// wave complete in program order, so the add of replica r+1 at some index sees the add of replica
+// r at the same index without a barrier, and inside one replica the indices are distinct.  Batches
+// follow each other in replica order with a workgroup barrier in between (the four waves take
+// turns, so that the messages of four batches are in flight at once).  Every element therefore
+// receives its addends in ascending replica order -- deterministic, no float atomics, no sort.
+constexpr int kAggBatch = 8;
+
 template <int QUANT, int KP>
-__device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_t kappa,
-                                                 uint32_t kappa_c, int n_replicas,
-                                                 const uint16_t* const* __restrict__ pairs_tab,
-                                                 const float* const* __restrict__ aux_tab, int lane) {
-    constexpr int kBatch = 8;
-    for (int r0 = 0; r0 < n_replicas; r0 += kBatch) {
-        uint32_t p[kBatch][KP];
-        float lo[kBatch], hi[kBatch], val[kBatch][KP];
+struct MessageBatch {
+    uint32_t p[kAggBatch][KP];
+    float lo[kAggBatch], hi[kAggBatch], val[kAggBatch][KP];
+
+    // Fetch replicas r0 .. r0+7 of chunk c (all loads issued together).
+    __device__ __forceinline__ void load(uint64_t c, uint32_t kappa, uint32_t kappa_c, int r0, int n_replicas,
+                                         const uint16_t* const* __restrict__ pairs_tab,
+                                         const float* const* __restrict__ aux_tab, int lane) {
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
+        for (int i = 0; i < kAggBatch; ++i) {
             lo[i] = hi[i] = 0.f;
+#pragma unroll
+            for (int k = 0; k < KP; ++k) { p[i][k] = 0xFFFFu; val[i][k] = 0.f; }
             if (r0 + i < n_replicas) {
                 const uint16_t* pr = pairs_tab[r0 + i] + c * kappa;
                 const float* ar = aux_tab[r0 + i];
@@ -634,13 +639,19 @@ __device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_
 #pragma unroll
                 for (int k = 0; k < KP; ++k) {
                     const uint32_t t = lane + 64 * k;
-                    p[i][k] = t < kappa_c ? (uint32_t)pr[t] : 0xFFFFu;
-                    val[i][k] = (QUANT == SPLC_QUANT_NONE && t < kappa_c) ? ar[c * kappa + t] : 0.f;
+                    if (t < kappa_c) {
+                        p[i][k] = pr[t];
+                        if (QUANT == SPLC_QUANT_NONE) val[i][k] = ar[c * kappa + t];
+                    }
                 }
             }
         }
+    }
+
+    // Add them to the accumulator, replica after replica.
+    __device__ __forceinline__ void apply(float* acc, uint32_t kappa_c, int r0, int n_replicas, int lane) const {
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
+        for (int i = 0; i < kAggBatch; ++i) {
             if (r0 + i < n_replicas) {
 #pragma unroll
                 for (int k = 0; k < KP; ++k) {
@@ -657,6 +668,26 @@ __device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_
                 }
             }
         }
+    }
+};
+
+// All lanes of the workgroup call this after the accumulator has been cleared (no barrier needed
+// before the call; one is taken inside before the first add).  Ends with a barrier.
+template <int QUANT, int KP>
+__device__ __forceinline__ void accumulate_chunk(float* acc, uint64_t c, uint32_t kappa, uint32_t kappa_c,
+                                                 int n_replicas, const uint16_t* const* __restrict__ pairs_tab,
+                                                 const float* const* __restrict__ aux_tab, int lane, int wave) {
+    const int n_batches = (n_replicas + kAggBatch - 1) / kAggBatch;
+    MessageBatch<QUANT, KP> mb;
+    if (wave < n_batches) mb.load(c, kappa, kappa_c, wave * kAggBatch, n_replicas, pairs_tab, aux_tab, lane);
+    __syncthreads();                                   // accumulator cleared by every lane
+    for (int g = 0; g < n_batches; ++g) {
+        if (wave == (g & 3)) {
+            mb.apply(acc, kappa_c, g * kAggBatch, n_replicas, lane);
+            if (g + 4 < n_batches)
+                mb.load(c, kappa, kappa_c, (g + 4) * kAggBatch, n_replicas, pairs_tab, aux_tab, lane);
+        }
+        __syncthreads();
     }
 }
 
@@ -687,7 +718,7 @@ __device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uin
 }
 
 // Line 5 of the update equations.  One workgroup per chunk; all lanes clear the 16 KB LDS
-// accumulator, wave 0 applies the messages, all lanes divide once by M and write.
+// accumulator, the waves apply the messages batch by batch, all lanes divide once by M and write.
 //   UPDATE = 0: delta_bar = acc / M is written densely (sparseloco_aggregate).
 //   UPDATE = 1: theta = fl(theta - fl(eta * delta_bar)) is applied in the same pass, and the new theta
 //               is also copied into n_reset further parameter sets (the replicas' theta_local, which
@@ -718,14 +749,17 @@ __device__ __forceinline__ void aggregate_body(float* acc, const ChunkDesc* __re
     }
 #pragma unroll
     for (int s = 0; s < 4; ++s) acc4[s * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
-    __syncthreads();
-    if (wave == 0) {
-        if (kappa_c <= 64) accumulate_chunk<QUANT, 1>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
-        else if (kappa_c <= 128) accumulate_chunk<QUANT, 2>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
-        else if (kappa_c <= 256) accumulate_chunk<QUANT, 4>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
-        else accumulate_chunk_any<QUANT>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+    if (kappa_c <= 64) {
+        accumulate_chunk<QUANT, 1>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane, wave);
+    } else if (kappa_c <= 128) {
+        accumulate_chunk<QUANT, 2>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane, wave);
+    } else if (kappa_c <= 256) {
+        accumulate_chunk<QUANT, 4>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane, wave);
+    } else {
+        __syncthreads();
+        if (wave == 0) accumulate_chunk_any<QUANT>(acc, c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        __syncthreads();
     }
-    __syncthreads();
     const float m = (float)n_replicas;
     if (VEC) {
 #pragma unroll
