@@ -23,6 +23,11 @@
  *     to wait for work that this plan enqueued 32 calls earlier.
  *   - A plan may be used from one host thread at a time and belongs to the
  *     device that was current when it was created.
+ *   - Calls that take a plan stage their pointer tables through pinned host
+ *     memory (one small asynchronous copy per call) and may wait on an event;
+ *     they are therefore not meant to be recorded into a HIP graph.  The
+ *     matrix entry points (sparseloco_reproject_embedding, sparseloco_subspace_*)
+ *     take no plan, only enqueue kernels, and can be captured.
  *   - Every function returns SPLC_OK or a negative status; nothing aborts or
  *     throws.  Arguments are validated on the host before anything is enqueued.
  *   - fp32 arithmetic is IEEE-754 round-to-nearest, one rounding per operation
