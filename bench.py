@@ -67,24 +67,43 @@ def cpu_baseline(rs, cfg, sample_tensors, quant=True, shapes=None):
         src = [[to_np(rs.theta_local[r][i]) for i in sample_tensors] for r in range(rs.R)]
     geo = dict(shapes=shapes, tile=64) if shapes is not None else {}
     threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
-    oracle.set_threads(threads)
-    t0 = time.perf_counter()
-    pairs, aux = [], []
-    for r in range(rs.R):
-        if rs.direct:
-            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], delta=src[r], quant=quant, **geo)
-        else:
-            p, a = oracle.compress(ef[r], cfg["kappa"], cfg["beta"], theta_outer=th, theta_local=src[r],
-                                   quant=quant, **geo)
-        pairs.append(p), aux.append(a)
-    dbar = oracle.aggregate(shapes if shapes is not None else numels, pairs, aux, cfg["kappa"], quant=quant,
-                            tile=64 if shapes is not None else None)
-    oracle.outer_update(th, dbar, cfg["outer_lr"])
-    dt = time.perf_counter() - t0
-    n = sum(numels)
-    return {"value": n / dt, "unit": "params/s", "cores": threads, "kind": "oracle",
-            "sample": "one full outer step (R=%d compress + aggregate + update) over %d tensors / %d params "
-                      "of the same workload (its first tensors in list order), %.1f s" % (rs.R, len(numels), n, dt)}
+
+    def one_outer_step(n_tensors, n_threads):
+        oracle.set_threads(n_threads)
+        th_ = [x.copy() for x in th[:n_tensors]]
+        ef_ = [[x.copy() for x in r[:n_tensors]] for r in ef]
+        g = dict(geo, shapes=geo["shapes"][:n_tensors]) if geo else {}
+        t0 = time.perf_counter()
+        pairs, aux = [], []
+        for r in range(rs.R):
+            if rs.direct:
+                p, a = oracle.compress(ef_[r], cfg["kappa"], cfg["beta"], delta=src[r][:n_tensors], quant=quant, **g)
+            else:
+                p, a = oracle.compress(ef_[r], cfg["kappa"], cfg["beta"], theta_outer=th_,
+                                       theta_local=src[r][:n_tensors], quant=quant, **g)
+            pairs.append(p), aux.append(a)
+        dbar = oracle.aggregate(g["shapes"] if g else numels[:n_tensors], pairs, aux, cfg["kappa"], quant=quant,
+                                tile=64 if g else None)
+        oracle.outer_update(th_, dbar, cfg["outer_lr"])
+        return sum(numels[:n_tensors]), time.perf_counter() - t0
+
+    n_all, dt_all = one_outer_step(len(numels), threads)
+    n_one, dt_one = one_outer_step(min(4, len(numels)), 1)
+    cpu = "unknown CPU"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"value": n_all / dt_all, "unit": "params/s", "cores": threads, "kind": "oracle",
+            "single_thread_value": n_one / dt_one,
+            "sample": "one full outer step (R=%d compress + aggregate + update) of the same workload over its first "
+                      "%d tensors / %d params on %d threads (%.1f s), and over its first %d tensors / %d params on "
+                      "1 thread (%.1f s); host: %s, %d logical CPUs"
+                      % (rs.R, len(numels), n_all, threads, dt_all, min(4, len(numels)), n_one, dt_one, cpu,
+                         os.cpu_count() or 0)}
 
 
 MFMA_FP32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
@@ -227,8 +246,8 @@ def main():
     ap.add_argument("--d-model", type=int, default=2048)
     ap.add_argument("--k", type=int, default=256)
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--kappa", type=int, default=None)
     ap.add_argument("--replicas", type=int, default=None)
