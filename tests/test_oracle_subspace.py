@@ -75,3 +75,28 @@ def test_projection_of_activations_closed_forms():
     # backward: plain product
     g = rng.standard_normal((rows, d))
     assert np.allclose(subspace.project(g, u), g[:, cols], rtol=0, atol=0)
+
+
+def test_heterogeneous_aggregation_bias_identity():
+    """Section 2.4, "Analysis of heterogeneous aggregation": with a fraction alpha of replicas sending
+    the unbiased pseudo-gradient D* and the rest its projection Pi_S(D*), the aggregate is
+    D* - (1 - alpha) B with B = D* - Pi_S(D*).  Checked through the outer-step oracle with everything
+    sent (kappa = chunk, Q = identity), where the mean is the plain mean of the messages."""
+    import oracle
+    rng = np.random.default_rng(8)
+    rows, d, k, M, n_full = 16, 16, 4, 8, 2                 # alpha = 2 / 8
+    u = subspace.orthonormal_basis(d, k, seed=1)
+    d_star = rng.standard_normal((rows, d))
+    d_proj, _ = subspace.reproject(d_star, np.zeros_like(d_star), u)        # Pi_S(D*)
+    bias = d_star - d_proj
+    pairs, values = [], []
+    for m in range(M):
+        delta = (d_star if m < n_full else d_proj).astype(np.float32).reshape(-1)
+        e = np.zeros(rows * d, np.float32)
+        p, v = oracle.compress([e], rows * d, 0.95, delta=[delta], chunk=rows * d, quant=False)
+        assert not e.any()
+        pairs.append(p), values.append(v)
+    mean = oracle.aggregate([rows * d], pairs, values, rows * d, chunk=rows * d, quant=False)[0].reshape(rows, d)
+    alpha = n_full / M
+    assert np.allclose(mean, d_star - (1 - alpha) * bias, atol=1e-6)
+    assert np.allclose(mean, alpha * d_star + (1 - alpha) * d_proj, atol=1e-6)
