@@ -1,11 +1,14 @@
 // SparseLoCo outer step for gfx950 (MI355X): kernels and C ABI.
 //
-// The three entry points follow the update equations of section 2.1 of the
-// paper (pseudo-gradient, error-feedback fold, chunk Top-kappa, Q, residual;
-// mean over replicas; outer SGD).  Nothing here is a dense contraction, so no
-// matrix cores are used: the kernels stream 16-byte-per-lane loads, keep each
-// 4096-element chunk in registers (16 values per lane, 256 lanes) and use LDS
-// only for the small hand-offs of the selection.
+// The entry points follow the update equations of section 2.1 of the paper:
+// compress (pseudo-gradient, error-feedback fold, chunk Top-kappa, Q, residual;
+// per replica, or for all replicas of a single-node simulation at once),
+// aggregate (mean over replicas), outer_update (outer SGD), and aggregate_update
+// (the last two in one pass).  Nothing here is a dense contraction, so no matrix
+// cores are used: the kernels stream 16-byte-per-lane non-temporal accesses, keep
+// each 4096-element chunk in registers (16 values per lane, 256 lanes) and use
+// LDS only for the small hand-offs of the selection and for the dense
+// accumulator of the mean.
 //
 // Element layout of a chunk inside a workgroup: lane `tid` holds, for slot
 // s = 0..3 and j = 0..3, local index  s*1024 + tid*4 + j  (one float4 per slot).
@@ -16,7 +19,6 @@
 // row segments).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <string.h>
 
 #include <algorithm>
 #include <new>
@@ -32,8 +34,8 @@ constexpr int kThreads = 256;            // one workgroup per chunk
 constexpr int kCandCap = 256;            // candidates the exact ranking handles (one per lane)
 constexpr int kFilterKappaMax = 256;     // the candidate filter needs kappa <= number of lanes
 constexpr int kSlots = 32;               // staging slots for pointer tables
-constexpr int kMaxReplicas = 1024;         // messages one aggregate call accepts
-constexpr int kMaxBatch = 64;              // replicas one compress_batch call accepts
+constexpr int kMaxReplicas = 1024;       // messages one aggregate call accepts
+constexpr int kMaxBatch = 64;            // replicas one compress_batch call accepts (and resets of aggregate_update)
 
 struct ChunkDesc {
     uint32_t tensor;                     // index into the pointer tables
