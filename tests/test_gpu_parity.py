@@ -241,3 +241,55 @@ def test_error_returns_do_not_launch():
         B.sparseloco_aggregate(plan, [], [], e)
     assert ei.value.status == B.SPLC_EINVAL
     plan.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations(seed):
+    """Seeded random tensor lists, kappa, replica counts, source modes, quantiser modes, layouts and
+    entry-point variants, each compared with the oracle element by element."""
+    rng = np.random.default_rng(9000 + seed)
+    tiled = bool(rng.integers(0, 2))
+    n_t = int(rng.integers(1, 6))
+    if tiled:
+        shapes = [(int(rng.integers(1, 200)), int(rng.integers(1, 200))) for _ in range(n_t)]
+        numels = None
+    else:
+        shapes = None
+        numels = [int(rng.choice([0, 1, 63, 64, 65, 4095, 4096, 4097, 8192, 3 * 4096 + int(rng.integers(0, 4096))]))
+                  for _ in range(n_t)]
+        if not any(numels):
+            numels[0] = 4096
+    kappa = int(rng.choice([1, 2, 7, 31, 32, 33, 64, 100, 128, 255, 256, 257, 1000]))
+    R = int(rng.integers(1, 6))
+    direct = [None, "f32", "bf16"][int(rng.integers(0, 3))]
+    quant = bool(rng.integers(0, 2))
+    heavy = bool(rng.integers(0, 2))
+    select = [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX][int(rng.integers(0, 4) == 0)]
+    fused = [None, "with_mean", "no_mean"][int(rng.integers(0, 3))]
+    batch = direct is None and bool(rng.integers(0, 2))
+    case = gaussian_case(numels, R=R, seed=int(rng.integers(0, 1 << 30)), direct=direct, heavy=heavy, shapes=shapes)
+    parity.check(case, kappa, lr=float(rng.choice([1.0, 0.8])), quant=quant, select=select, fused=fused, batch=batch,
+                 outer_steps=int(rng.integers(1, 3)),
+                 what="random case %d (tiled=%s kappa=%d R=%d direct=%s quant=%s)" % (seed, tiled, kappa, R, direct, quant))
+
+
+def test_aggregate_survives_malformed_messages():
+    """Pairs that no compress call would emit (duplicate indices, spare bits set, indices beyond a partial
+    chunk): indices are masked to 12 bits and only present positions are written, so the call completes;
+    the values themselves are unspecified, positions outside every chunk's extent stay untouched."""
+    import torch
+    numels = [4096 * 2 + 100, 50]
+    kappa, R = 64, 3
+    plan = B.Plan(numels, kappa)
+    g = torch.Generator(device="cuda").manual_seed(1)
+    pairs = [torch.randint(-32768, 32767, (plan.num_chunks * kappa,), generator=g, device="cuda",
+                           dtype=torch.int16) for _ in range(R)]
+    scales = [torch.rand(plan.num_chunks * 2, generator=g, device="cuda") for _ in range(R)]
+    guard = 7.0
+    bufs = [torch.full((n + 64,), guard, device="cuda") for n in numels]
+    dbar = [b[:n] for b, n in zip(bufs, numels)]
+    B.sparseloco_aggregate(plan, pairs, scales, dbar)
+    torch.cuda.synchronize()
+    for b, n in zip(bufs, numels):
+        assert bool(torch.isfinite(b[:n]).all()) and bool((b[n:] == guard).all())
+    plan.close()
