@@ -328,6 +328,216 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
     }
 }
 
+// Projection onto a narrow basis: out[rows, k] = (x - T_perp[token] - PosEmbed) U with k <= 16 * NB <= 64
+// (section 2.2; the subspace dimensions the paper sweeps are d/8 ... d/768, so most of them land here).
+// With so few output columns the product is bound by reading x (and the gathered table rows) once, not
+// by the matrix pipe, and the wide GEMM tile above would spend most of its MFMAs on columns that do not
+// exist.  So: v_mfma_f32_16x16x4_f32, one workgroup per 16 rows, and the four waves split the reduction
+// dimension between them (wave w takes the 32-wide d tiles w, w + 4, ...), which gives four times the
+// waves to keep HBM busy.  Inside the loop a wave synchronises with nobody:
+//   * its x / table values go from global memory straight into the A operand layout.  Lane (g, c)
+//     (g = lane / 16, c = lane % 16) loads four consecutive floats d0 + 4g .. 4g + 3 of row c; MFMA step
+//     s then multiplies the set {d0 + 4g + s}, a permutation of a group of sixteen d that the B operand
+//     follows -- a sum does not care which four d share a step;
+//   * its own U tile (32 x k floats, L2 resident) goes through a private, double-buffered LDS slab whose
+//     row pitch 16 NB + 4 makes the operand reads (rows 4g + s, columns c) conflict free.
+// PD tiles of A loads are in flight per wave.  At the end the four partial sums meet in LDS and are
+// added in wave order, so the result does not depend on timing.
+// d must be a multiple of 32 (whole tiles: no load needs a guard); other d go to the general kernel.
+// TP / PE: a T_perp table / a positional table is subtracted.  They are template parameters, not run-time
+// tests, so that the number of loads in flight is known at every point of the loop and a wait can name
+// the oldest load instead of draining the queue.
+template <int NB, int PD, bool TP, bool PE>
+__global__ __launch_bounds__(kThreads, NB == 1 ? 4 : (NB == 2 ? 3 : 2)) void project_narrow_kernel(
+    const float* __restrict__ x, HighRank h, const float* __restrict__ u, float* __restrict__ out, int rows, int d,
+    int k) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    constexpr int KT = 32;                       // d values per tile: one 128-byte line of every row
+    constexpr int KP = 16 * NB + 4;              // LDS pitch of a U tile row
+    constexpr int NLD = KT * 16 * NB / 256;      // 16-byte load instructions per U tile
+    static_assert(PD == 2 || PD == 4, "the LDS buffer parity follows the stage index");
+    __shared__ __attribute__((aligned(16))) float slab[4][2][KT * KP];
+    static_assert(sizeof(float) * 4 * 2 * KT * KP >= sizeof(float) * 4 * NB * 256, "partial sums reuse the slab");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // tile indices stay in scalar registers
+    const int g = lane >> 4, c = lane & 15;
+    const int r0 = blockIdx.x * 16;
+    const int row = r0 + c < rows ? r0 + c : rows - 1;         // rows past the end repeat the last one; never stored
+    const float* const px = x + (int64_t)row * d + 4 * g;
+    const float* const pt = TP ? h.perp_row(row) + 4 * g : nullptr;
+    const float* const pp = PE ? h.pos_row(row) + 4 * g : nullptr;
+    const int n_tiles = d / KT;
+
+    struct Stage { vfloat4 x[2], t[2], p[2]; };
+    Stage st[PD];
+    vfloat4 ur[NLD];
+    v4f acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    auto fetch_a = [&](int t, Stage& q) {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int at = t * KT + 16 * hh;
+            q.x[hh] = ldg4(px + at);
+            if (TP) q.t[hh] = ldg4(pt + at);
+            if (PE) q.p[hh] = ldg4(pp + at);
+        }
+    };
+    // A U tile -- 32 rows of k floats -- is one contiguous run of 32 k floats in memory (16-byte aligned when U
+    // is) whatever k is, so it is loaded flat, four floats per lane and instruction, and each float finds its
+    // (row, column) slot of the padded slab by a division by k (multiply-high with a reciprocal that is exact
+    // for the 2048 positions of a tile).  A lane whose position lies beyond the tile (k < 16 NB) loads the
+    // tile's first floats instead and stores nothing.
+    const uint32_t kinv = ((1u << 20) + (uint32_t)k - 1) / (uint32_t)k;
+    const uint32_t tile_floats = (uint32_t)(KT * k);
+    auto fetch_u = [&](int t) {
+        const float* base = u + (int64_t)t * tile_floats;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const uint32_t f = 4 * (lane + 64 * i);
+            // a basis of this column-block count has more than 16 (NB - 1) columns, which puts the first
+            // 2 (NB - 1) loads of every lane inside the tile
+            ur[i] = ldg4(base + ((i < 2 * (NB - 1) || f < tile_floats) ? f : 0u));
+        }
+    };
+    const bool k_by_4 = (k & 3) == 0;             // then the four floats of a load share a row of U
+    auto stash_u = [&](int buf) {
+        float* const tile_base = &slab[wave][buf][0];
+        // Lanes beyond the tile store too -- into the four padding floats at the end of a slab row, which
+        // nobody reads: a store under a condition would drag its load into the conditional block, and the
+        // wait for that load with it.
+        float* const spare = tile_base + (lane & 31) * KP + 16 * NB;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            uint32_t f = 4 * (lane + 64 * i);
+            asm volatile("" : "+v"(f));           // recompute the slot every time instead of keeping NLD addresses live
+            const bool inside = i < 2 * (NB - 1) || f < tile_floats;
+            const uint32_t r = (f * kinv) >> 20;
+            uint32_t col = f - r * (uint32_t)k;
+            float* dst = tile_base + r * KP + col;
+            if (k_by_4) {
+                *reinterpret_cast<v4f*>(inside ? dst : spare) = v4f{ur[i][0], ur[i][1], ur[i][2], ur[i][3]};
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    *(inside ? dst : spare + j) = ur[i][j];
+                    ++col;
+                    dst += col == (uint32_t)k ? KP - k + 1 : 1;
+                    col = col == (uint32_t)k ? 0 : col;
+                }
+            }
+        }
+    };
+    auto multiply = [&](const Stage& q, int buf) {
+        // all B operands of the tile are requested from LDS before the first MFMA, so that the matrix pipe
+        // does not wait for them one pair at a time
+        const float* b0 = &slab[wave][buf][4 * g * KP + c];
+        float b[2][4][NB];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) b[hh][s][nb] = b0[(16 * hh + s) * KP + 16 * nb];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            vfloat4 a = q.x[hh];
+            if (TP) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = __fsub_rn(a[i], q.t[hh][i]);
+            }
+            if (PE) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = __fsub_rn(a[i], q.p[hh][i]);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[hh][s][nb], acc[nb], 0, 0, 0);
+        }
+    };
+
+    // Wave w owns the n_mine tiles w, w + 4, ...; its i-th tile uses A stage i % PD and LDS buffer i % 2.
+    // Inside the loop every load is issued unconditionally -- near the end it simply repeats the last tile,
+    // whose data nobody uses -- for the same reason as above: a known number of loads in flight.
+    const int n_mine = wave < n_tiles ? (n_tiles - wave + 3) >> 2 : 0;
+    const int t_last = wave + 4 * (n_mine - 1);
+    auto tile = [&](int i) { const int t = wave + 4 * i; return t < t_last ? t : t_last; };
+    auto step = [&](int i, int j) {
+        // After this tile's products are issued, the next tile's U -- requested one iteration ago -- moves to
+        // the other LDS buffer (whose reads were issued an iteration ago; a wave's LDS operations keep their
+        // order), and the tile after that starts its way from L2.
+        multiply(st[j], j & 1);
+        stash_u((j & 1) ^ 1);
+        fetch_u(tile(i + 2));
+        fetch_a(tile(i + PD), st[j]);
+    };
+    if (n_mine > 0) {
+        fetch_u(wave);
+#pragma unroll
+        for (int j = 0; j < PD; ++j) fetch_a(tile(j), st[j]);
+        stash_u(0);
+        fetch_u(tile(1));
+        int i = 0;
+        for (; i + PD <= n_mine; i += PD) {
+#pragma unroll
+            for (int j = 0; j < PD; ++j) step(i + j, j);
+        }
+#pragma unroll
+        for (int j = 0; j < PD - 1; ++j)
+            if (i + j < n_mine) step(i + j, j);
+    }
+
+    // D layout of the 16 x 16 MFMA: register v of lane l holds row 4 (l / 16) + v, column l % 16.
+    __syncthreads();
+    float* part = &slab[0][0][0];                 // [wave][nb][row][col]
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part[((wave * NB + nb) * 16 + 4 * g + v) * 16 + c] = acc[nb][v];
+    __syncthreads();
+    const int orow = tid >> 4, oc = tid & 15;
+    if (r0 + orow < rows) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int col = 16 * nb + oc;
+            if (col < k) {
+                float sum = part[((0 * NB + nb) * 16 + orow) * 16 + oc];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) sum = __fadd_rn(sum, part[((w * NB + nb) * 16 + orow) * 16 + oc]);
+                out[(int64_t)(r0 + orow) * k + col] = sum;
+            }
+        }
+    }
+}
+
+template <bool TP, bool PE>
+void launch_project_narrow_tables(const float* x, const HighRank& h, const float* u, float* out, int rows, int d,
+                                  int k, hipStream_t st) {
+    const dim3 grid((unsigned)((rows + 15) / 16)), block(kThreads);
+    const int nb = (k + 15) / 16;
+    if (nb == 1)
+        hipLaunchKernelGGL((project_narrow_kernel<1, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
+    else if (nb == 2)
+        hipLaunchKernelGGL((project_narrow_kernel<2, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
+    else if (nb == 3)
+        hipLaunchKernelGGL((project_narrow_kernel<3, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
+    else
+        hipLaunchKernelGGL((project_narrow_kernel<4, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
+}
+void launch_project_narrow(const float* x, const HighRank& h, const float* u, float* out, int rows, int d, int k,
+                           hipStream_t st) {
+    if (h.t_perp && h.pos) launch_project_narrow_tables<true, true>(x, h, u, out, rows, d, k, st);
+    else if (h.t_perp) launch_project_narrow_tables<true, false>(x, h, u, out, rows, d, k, st);
+    else if (h.pos) launch_project_narrow_tables<false, true>(x, h, u, out, rows, d, k, st);
+    else launch_project_narrow_tables<false, false>(x, h, u, out, rows, d, k, st);
+}
+// The narrow kernel takes bases of at most 64 columns over a whole number of 32-wide d tiles.
+bool narrow_applies(int d, int k) { return k <= 64 && d % 32 == 0; }
+
 // Launch with the 128-row tile, or the 64-row tile when that is needed to give every compute unit
 // several workgroups.
 template <bool B_NK, class Pro, class Epi>
@@ -358,7 +568,10 @@ extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const f
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int M = (int)vocab;
     // pass 1: coeff = T_S U            (M x k) = (M x d)(d x k)
-    launch_gemm<false>(t_s, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k}, st);
+    if (narrow_applies(d, k))
+        launch_project_narrow(t_s, HighRank{nullptr, nullptr, 0, nullptr, 1, (int64_t)d}, u, coeff_ws, M, d, k, st);
+    else
+        launch_gemm<false>(t_s, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k}, st);
     // pass 2: Pi = coeff U^T           (M x d) = (M x k)(k x d), U given as d x k = the N x K form
     launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{},
                       UpdateEmbedding{t_s, t_perp, (int64_t)d}, st);
@@ -387,7 +600,9 @@ extern "C" int sparseloco_subspace_project(const float* x, const float* t_perp, 
     const int M = (int)rows;
     const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (t_perp || pos_embed)
+    if (narrow_applies(d, k)) {
+        launch_project_narrow(x, h, u, x_tilde, M, d, k, st);
+    } else if (t_perp || pos_embed)
         launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank{h, {nullptr, nullptr}},
                            StoreCoeff{x_tilde, (int64_t)k}, st);
     else

@@ -83,7 +83,12 @@ def test_argument_checks():
 
 @pytest.mark.parametrize("rows,seq,d,k,vocab,use_perp,use_pos", [
     (256, 64, 128, 16, 50, True, True), (300, 100, 200, 7, 33, True, True), (129, 43, 130, 130, 5, True, False),
-    (512, 128, 768, 96, 1000, False, True), (1000, 250, 1536, 2, 64, True, True), (640, 64, 2048, 256, 512, False, False)])
+    (512, 128, 768, 96, 1000, False, True), (1000, 250, 1536, 2, 64, True, True), (640, 64, 2048, 256, 512, False, False),
+    # bases of at most 64 columns take the narrow kernel: every column-block count, reduction lengths that
+    # leave some of a workgroup's waves without a tile or end inside a tile, row counts off the 16-row grid
+    (257, 64, 100, 33, 20, True, False), (64, 16, 36, 36, 7, False, True), (1000, 128, 512, 64, 100, True, True),
+    (33, 33, 70, 48, 9, True, True), (500, 50, 2048, 17, 30, False, False), (16, 16, 1, 1, 3, True, True),
+    (4099, 1024, 1536, 8, 3000, True, True), (15, 5, 257, 64, 4, False, False), (2048, 512, 768, 32, 500, False, True)])
 def test_project_and_reconstruct_match_the_oracle(rows, seq, d, k, vocab, use_perp, use_pos):
     rng = np.random.default_rng(rows + d + k)
     u64 = subspace.orthonormal_basis(d, k, rows)
