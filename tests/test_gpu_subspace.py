@@ -45,7 +45,10 @@ def run_case(vocab, d, k, seed):
 
 
 @pytest.mark.parametrize("vocab,d,k", [(128, 128, 128), (256, 256, 32), (300, 200, 7), (1, 64, 2), (129, 130, 131),
-                                       (1000, 768, 96), (517, 1536, 2), (64, 2048, 256), (2000, 1024, 128)])
+                                       (1000, 768, 96), (517, 1536, 2), (64, 2048, 256), (2000, 1024, 128),
+                                       # narrow bases: both passes (k <= 32 in fours, or k <= 8), pass 1 only (k <= 64)
+                                       (100, 64, 8), (33, 96, 20), (2000, 1024, 16), (70, 32, 32), (300, 128, 64),
+                                       (17, 160, 5), (4097, 512, 4), (250, 2048, 48)])
 def test_reproject_matches_the_oracle(vocab, d, k):
     if k > d:
         k = d
@@ -88,7 +91,11 @@ def test_argument_checks():
     # leave some of a workgroup's waves without a tile or end inside a tile, row counts off the 16-row grid
     (257, 64, 100, 33, 20, True, False), (64, 16, 36, 36, 7, False, True), (1000, 128, 512, 64, 100, True, True),
     (33, 33, 70, 48, 9, True, True), (500, 50, 2048, 17, 30, False, False), (16, 16, 1, 1, 3, True, True),
-    (4099, 1024, 1536, 8, 3000, True, True), (15, 5, 257, 64, 4, False, False), (2048, 512, 768, 32, 500, False, True)])
+    (4099, 1024, 1536, 8, 3000, True, True), (15, 5, 257, 64, 4, False, False), (2048, 512, 768, 32, 500, False, True),
+    # the narrow reconstruction: k in fours up to 32, or any k up to 8 loaded one by one; single rows and tiles
+    (77, 11, 64, 3, 9, True, False), (200, 40, 96, 5, 50, False, False), (333, 37, 256, 24, 100, True, True),
+    (50, 50, 32, 12, 5, False, True), (1, 1, 32, 4, 2, True, True), (130, 13, 160, 1, 7, True, True),
+    (1000, 100, 1024, 20, 300, True, False)])
 def test_project_and_reconstruct_match_the_oracle(rows, seq, d, k, vocab, use_perp, use_pos):
     rng = np.random.default_rng(rows + d + k)
     u64 = subspace.orthonormal_basis(d, k, rows)
