@@ -4,7 +4,8 @@
 //
 // Two dense contractions, so this part does use the matrix cores: fp32 MFMA
 // (v_mfma_f32_32x32x2_f32, fp32 accumulation), LDS-tiled, 128 x 128 output tile per
-// 256-lane workgroup, each wave a 64 x 64 quarter (2 x 2 MFMA tiles).
+// 256-lane workgroup, each wave a 64 x 64 quarter (2 x 2 MFMA tiles); 64-row and 64-column
+// tiles for the skinny shapes.
 //   pass 1:  C = T_S U                       (vocab x k, caller's workspace)
 //   pass 2:  R = C U^T, fused with the update of T_perp and T_S (R is never stored separately)
 //
@@ -23,8 +24,7 @@
 
 namespace {
 
-constexpr int TM = 128, TN = 128, TK = 16;
-constexpr int PITCH = TM + 4;            // LDS row pitch in floats (TM == TN)
+constexpr int TM = 128, TK = 16;         // largest M tile (bounds the row counts accepted), K tile
 constexpr int kThreads = 256;
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -46,6 +46,19 @@ __device__ __forceinline__ void load8(const float* __restrict__ base, int64_t ld
         for (int i = 0; i < 8; ++i)
             out[i] = (row < rows && col + i < cols) ? base[(int64_t)row * ld + col + i] : 0.f;
     }
+}
+
+// The same for four floats (into the first four slots; the rest are not used).
+__device__ __forceinline__ void load4(const float* __restrict__ base, int64_t ld, int row, int col, int rows,
+                                      int cols, float (&out)[8]) {
+    if (row < rows && col + 4 <= cols) {
+        const vfloat4 a = *(const SPLC_GLOBAL vfloat4*)(base + (int64_t)row * ld + col);
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = (row < rows && col + i < cols) ? base[(int64_t)row * ld + col + i] : 0.f;
+    }
+    out[4] = out[5] = out[6] = out[7] = 0.f;
 }
 
 __device__ __forceinline__ vfloat4 ldg4(const float* p) { return *(const SPLC_GLOBAL vfloat4*)p; }
@@ -193,37 +206,39 @@ struct AddHighRank {
 // B_NK = true: B is given as its transpose, row-major N x K (ldb), i.e. B[k][n] = Bt[n][k].
 // The A values pass through pro(row, col, M, K, values[8]) on their way in; the output goes
 // through epi(row, col, four values, N).
-template <int TM_, bool B_NK, class Pro, class Epi>
+template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
 __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restrict__ A, int64_t lda,
                                                             const float* __restrict__ B, int64_t ldb, int M, int N,
                                                             int K, Pro pro, Epi epi) {
-    // TM_ x 128 output tile; the four waves form a 2 x 2 grid, each with MI x 2 MFMA tiles of 32 x 32
-    // (MI = 2 for TM_ = 128, MI = 1 for TM_ = 64, which gives small problems twice the workgroups).
-    static_assert(TM_ == 128 || TM_ == 64, "supported M tiles");
-    constexpr int MI = TM_ / 64;
-    constexpr int AF = TM_ / 16;             // floats of the A tile per lane: 8 or 4
-    __shared__ float As[2][TK][PITCH];
-    __shared__ float Bs[2][TK][PITCH];
+    // TM_ x TN_ output tile; the four waves form a 2 x 2 grid, each with MI x NJ MFMA tiles of 32 x 32
+    // (128 x 128: 2 x 2 per wave; the smaller tiles give small problems more workgroups and waste less of
+    // the last column tile when N is a multiple of 64 only).
+    static_assert((TM_ == 128 || TM_ == 64) && (TN_ == 128 || TN_ == 64), "supported tiles");
+    constexpr int MI = TM_ / 64, NJ = TN_ / 64;
+    constexpr int AF = TM_ / 16, BF = TN_ / 16;      // floats of the A / B tile per lane: 8 or 4
+    constexpr int PA = TM_ + 4, PB = TN_ + 4;        // LDS row pitches in floats
+    __shared__ float As[2][TK][PA];
+    __shared__ float Bs[2][TK][PB];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
-    const int m0 = blockIdx.y * TM_, n0 = blockIdx.x * TN;
+    const int m0 = blockIdx.y * TM_, n0 = blockIdx.x * TN_;
 
-    v16f acc[MI][2];
+    v16f acc[MI][NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Staging assignment.  "Row-of-k" tiles (A always, B when given as N x K): lane t takes one matrix
-    // row and AF (A) or eight (B) consecutive k.  "k-major" tiles (B as K x N): lane t takes
-    // k = t / 16 and eight consecutive n.
+    // Staging assignment.  "Row-of-k" tiles (A always, B when given as N x K): a lane takes one matrix
+    // row and AF (A) or BF (B) consecutive k.  "k-major" tiles (B as K x N): lane t takes k = t / 16 and
+    // BF consecutive n.
     const int ar = tid / (TK / AF), ak = (tid % (TK / AF)) * AF;
-    const int br = tid >> 1, bkk = (tid & 1) * 8;
-    const int bk = tid >> 4, bn = (tid & 15) * 8;
+    const int br = tid / (TK / BF), bkk = (tid % (TK / BF)) * BF;
+    const int bk = tid >> 4, bn = (tid & 15) * BF;
     // Global loads run two K tiles ahead of the MFMAs (one tile of matrix work is shorter than the
     // memory latency): tile t+2 is fetched into registers while tile t is multiplied and tile t+1,
     // fetched one iteration earlier, waits in a second register set for its turn to go to LDS.
@@ -233,31 +248,26 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
             load8(A, lda, m0 + ar, k0 + ak, M, K, qa);
             pro(m0 + ar, k0 + ak, M, K, qa);
         } else {
-            // half a load8: the upper four values are not used
-            const int row = m0 + ar, col = k0 + ak;
-            if (row < M && col + 4 <= K) {
-                const vfloat4 v = ldg4(A + (int64_t)row * lda + col);
-                qa[0] = v.x; qa[1] = v.y; qa[2] = v.z; qa[3] = v.w;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    qa[i] = (row < M && col + i < K) ? A[(int64_t)row * lda + col + i] : 0.f;
-            }
-            qa[4] = qa[5] = qa[6] = qa[7] = 0.f;
-            pro.four(row, col, M, K, qa);
+            load4(A, lda, m0 + ar, k0 + ak, M, K, qa);
+            pro.four(m0 + ar, k0 + ak, M, K, qa);
         }
-        if (B_NK) load8(B, ldb, n0 + br, k0 + bkk, N, K, qb);
-        else load8(B, ldb, k0 + bk, n0 + bn, K, N, qb);
+        if (B_NK) {
+            if (BF == 8) load8(B, ldb, n0 + br, k0 + bkk, N, K, qb);
+            else load4(B, ldb, n0 + br, k0 + bkk, N, K, qb);
+        } else {
+            if (BF == 8) load8(B, ldb, k0 + bk, n0 + bn, K, N, qb);
+            else load4(B, ldb, k0 + bk, n0 + bn, K, N, qb);
+        }
     };
     auto stash = [&](int buf, const float (&qa)[8], const float (&qb)[8]) {
 #pragma unroll
         for (int i = 0; i < AF; ++i) As[buf][ak + i][ar] = qa[i];
         if (B_NK) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) Bs[buf][bkk + i][br] = qb[i];
+            for (int i = 0; i < BF; ++i) Bs[buf][bkk + i][br] = qb[i];
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) Bs[buf][bk][bn + i] = qb[i];
+            for (int i = 0; i < BF; ++i) Bs[buf][bk][bn + i] = qb[i];
         }
     };
 
@@ -274,12 +284,12 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
         // The operands of the next k pair are read from LDS before the MFMAs of the current pair are
         // issued, so that the LDS latency hides behind the matrix pipe.
         const int kq = lane >> 5, rc = lane & 31;
-        float fa[2][MI], fb[2][2];
+        float fa[2][MI], fb[2][NJ];
         auto operands = [&](int kk, int st) {
 #pragma unroll
             for (int i = 0; i < MI; ++i) fa[st][i] = As[buf][kk + kq][wm * (32 * MI) + 32 * i + rc];
-            fb[st][0] = Bs[buf][kk + kq][wn * 64 + rc];
-            fb[st][1] = Bs[buf][kk + kq][wn * 64 + 32 + rc];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) fb[st][j] = Bs[buf][kk + kq][wn * (32 * NJ) + 32 * j + rc];
         };
         operands(0, 0);
 #pragma unroll
@@ -288,10 +298,10 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
             if (p + 1 < TK / 2) operands(2 * (p + 1), st ^ 1);
             __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the MFMAs below
 #pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][i], fb[st][0], acc[i][0], 0, 0, 0);
-                acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][i], fb[st][1], acc[i][1], 0, 0, 0);
-            }
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][i], fb[st][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (t + 1 < n_tiles) stash(buf ^ 1, ra[0], rb[0]);
@@ -301,29 +311,30 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
     }
 
     // Epilogue through LDS, 32 output rows at a time, so that global memory sees whole rows
-    // (16 bytes per lane, 512 bytes per row) instead of the MFMA result layout, in which register v
-    // of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32].  The slab reuses the A staging
+    // (16 bytes per lane, 4 TN_ bytes per row) instead of the MFMA result layout, in which register v
+    // of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32].  The slab reuses the B staging
     // buffers (same size); the K loop ended with a barrier, so they are free.
-    float* slab = &As[0][0][0];
-    static_assert(2 * TK * PITCH >= 32 * PITCH, "slab must fit the A staging buffers");
+    float* slab = &Bs[0][0][0];
+    static_assert(2 * TK * PB >= 32 * PB, "slab must fit the B staging buffers");
 #pragma unroll
     for (int s = 0; s < TM_ / 32; ++s) {
         if (wm == s / MI) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    slab[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * PITCH + wn * 64 + j * 32 + (lane & 31)] =
+                    slab[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * PB + wn * (32 * NJ) + j * 32 + (lane & 31)] =
                         acc[s % MI][j][v];
         }
         __syncthreads();
+        constexpr int VPR = TN_ / 4;                // 16-byte pieces per slab row
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 32 * VPR / kThreads; ++q) {
             const int f = tid + kThreads * q;
-            const int r = f >> 5, c4 = (f & 31) * 4;
+            const int r = f / VPR, c4 = (f % VPR) * 4;
             const int row = m0 + 32 * s + r, col = n0 + c4;
             if (row < M && col < N) {
-                const float* src = slab + r * PITCH + c4;
+                const float* src = slab + r * PB + c4;
                 vfloat4 v = {src[0], src[1], src[2], src[3]};
                 epi(row, col, v, N);
             }
@@ -696,21 +707,36 @@ bool narrow_reconstruct_applies(int d, int k) { return d % 32 == 0 && ((k % 4 ==
 // The narrow projection takes bases of at most 64 columns over a whole number of 32-wide d tiles.
 bool narrow_applies(int d, int k) { return k <= 64 && d % 32 == 0; }
 
-// Launch with the 128-row tile, or the 64-row tile when that is needed to give every compute unit
-// several workgroups.
+template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
+void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
+                      hipStream_t st) {
+    dim3 grid((unsigned)((N + TN_ - 1) / TN_), (unsigned)((M + TM_ - 1) / TM_));
+    hipLaunchKernelGGL((gemm_f32_kernel<TM_, TN_, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B, ldb, M, N,
+                       K, pro, epi);
+}
+// Tile choice (measured on the shapes of sections 2.2 and 2.4 at d 1536 / 2048, k = d/8 ... d/16):
+//   columns: 64 wide when N spans an odd number of 64-column blocks (the last 128-wide tile would be at
+//            most half used), else 128 wide;
+//   rows:    128 when that still leaves two workgroups per compute unit, else 64;
+//   short_k_light_epilogue (the reconstruction: K = k, one store per output): 64-row tiles always and
+//            64 columns up to K = 192 -- with so short a K loop more, smaller workgroups per compute unit
+//            overlap one group's epilogue with another's products.
 template <bool B_NK, class Pro, class Epi>
 void launch_gemm(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
-                 hipStream_t st) {
-    const int64_t wg128 = (int64_t)((M + 127) / 128) * ((N + TN - 1) / TN);
-    if (wg128 >= 4 * 256) {
-        dim3 grid((unsigned)((N + TN - 1) / TN), (unsigned)((M + 127) / 128));
-        hipLaunchKernelGGL((gemm_f32_kernel<128, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B, ldb, M, N, K,
-                           pro, epi);
+                 hipStream_t st, bool short_k_light_epilogue = false) {
+    auto groups = [&](int tm, int tn) { return (int64_t)((M + tm - 1) / tm) * ((N + tn - 1) / tn); };
+    bool wide = ((N + 63) / 64) % 2 == 0;
+    bool tall;
+    if (short_k_light_epilogue) {
+        wide = K > 192;
+        tall = false;
     } else {
-        dim3 grid((unsigned)((N + TN - 1) / TN), (unsigned)((M + 63) / 64));
-        hipLaunchKernelGGL((gemm_f32_kernel<64, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B, ldb, M, N, K,
-                           pro, epi);
+        tall = groups(128, wide ? 128 : 64) >= 2 * 256;
     }
+    if (tall && wide) launch_gemm_tile<128, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
+    else if (tall) launch_gemm_tile<128, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
+    else if (wide) launch_gemm_tile<64, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
+    else launch_gemm_tile<64, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
 }
 
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
@@ -787,6 +813,6 @@ extern "C" int sparseloco_subspace_reconstruct(const float* x_tilde, const float
     if (narrow_reconstruct_applies(d, k))
         launch_reconstruct_narrow(x_tilde, h, u, x_hat, nullptr, M, d, k, st);
     else
-        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat}, st);
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat}, st, true);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
