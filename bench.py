@@ -262,8 +262,11 @@ def main():
     ap.add_argument("--d-model", type=int, default=2048)
     ap.add_argument("--k", type=int, default=256)
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default 20; 200 for the sub-millisecond --op reproject / project)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed steps before (default 3; 50 for --op reproject / project, whose 20-step run "
+                         "would be over before the GPU has left its idle clocks)")
     ap.add_argument("--workload", type=int, default=2)
     ap.add_argument("--kappa", type=int, default=None)
     ap.add_argument("--replicas", type=int, default=None)
@@ -275,6 +278,11 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
+    short_op = args.op != "outer_step"
+    if args.steps is None:
+        args.steps = 200 if short_op else 20
+    if args.warmup is None:
+        args.warmup = 50 if short_op else 3
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
