@@ -20,6 +20,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "sparseloco.h"
 
 namespace {
@@ -31,38 +33,31 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float vfloat4 __attribute__((ext_vector_type(4), aligned(4)));
 #define SPLC_GLOBAL __attribute__((address_space(1)))
 
-// Eight consecutive floats of row `row` starting at column `col` of a row-major matrix
-// (rows x cols, leading dimension ld); zeros outside the matrix.
-__device__ __forceinline__ void load8(const float* __restrict__ base, int64_t ld, int row, int col, int rows,
-                                      int cols, float (&out)[8]) {
-    if (row < rows && col + 8 <= cols) {
-        const float* p = base + (int64_t)row * ld + col;
-        vfloat4 a = *(const SPLC_GLOBAL vfloat4*)p;
-        vfloat4 b = *(const SPLC_GLOBAL vfloat4*)(p + 4);
-        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
-        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            out[i] = (row < rows && col + i < cols) ? base[(int64_t)row * ld + col + i] : 0.f;
-    }
-}
-
-// The same for four floats (into the first four slots; the rest are not used).
-__device__ __forceinline__ void load4(const float* __restrict__ base, int64_t ld, int row, int col, int rows,
-                                      int cols, float (&out)[8]) {
-    if (row < rows && col + 4 <= cols) {
-        const vfloat4 a = *(const SPLC_GLOBAL vfloat4*)(base + (int64_t)row * ld + col);
-        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) out[i] = (row < rows && col + i < cols) ? base[(int64_t)row * ld + col + i] : 0.f;
-    }
-    out[4] = out[5] = out[6] = out[7] = 0.f;
-}
-
 __device__ __forceinline__ vfloat4 ldg4(const float* p) { return *(const SPLC_GLOBAL vfloat4*)p; }
 __device__ __forceinline__ void stg4(float* p, vfloat4 v) { *(SPLC_GLOBAL vfloat4*)p = v; }
+
+// F (4 or 8) consecutive floats row[col .. col + F - 1] of a matrix row with `cols` columns, into out[0 .. F-1].
+// GUARD = false: the caller knows that they all exist -- plain 16-byte loads, no branch (the compiler can then
+// count the loads in flight and wait for the oldest alone).  GUARD = true: element by element, zeros from
+// column `cols` on, 16-byte loads where a lane's values all exist (the K tail, and the workgroups on the right
+// edge of B).
+template <int F, bool GUARD>
+__device__ __forceinline__ void row_load(const float* __restrict__ row, int col, int cols, float (&out)[8]) {
+    if (!GUARD) {
+        const vfloat4 a = ldg4(row + col);
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        if (F == 8) {
+            const vfloat4 b = ldg4(row + col + 4);
+            out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+        }
+    } else if (col + F <= cols) {
+        row_load<F, false>(row, col, cols, out);
+    } else {
+#pragma unroll
+        for (int i = 0; i < F; ++i) out[i] = col + i < cols ? row[col + i] : 0.f;
+    }
+}
+
 
 // Epilogues receive four consecutive columns of one output row (col is a multiple of 4; columns
 // at or beyond n_cols do not exist).
@@ -126,47 +121,43 @@ struct HighRank {
     __device__ __forceinline__ const float* pos_row(int row) const { return pos + (int64_t)(row % seq_len) * ld; }
 };
 
-// A-operand prologues: called with the eight loaded values of (row, col .. col+7).
+// A-operand prologues.  fetch() issues the loads of whatever is combined with F values (row, col .. col+F-1)
+// of A; apply() combines them when the values go to LDS, one K tile later -- kept apart so that a tile's
+// loads stay in flight while the previous tile is multiplied.  prepare() is called once per lane with the
+// (valid) matrix row that the lane stages.
 struct NoPrologue {
-    __device__ __forceinline__ void prepare(int, int) {}
-    __device__ __forceinline__ void operator()(int, int, int, int, float (&)[8]) const {}
-    __device__ __forceinline__ void four(int, int, int, int, float (&)[8]) const {}
+    static constexpr int kTables = 0;
+    __device__ __forceinline__ void prepare(int) {}
+    template <int F, bool GUARD>
+    __device__ __forceinline__ void fetch(int, int, float (&)[2][8]) const {}
+    template <int F>
+    __device__ __forceinline__ void apply(float (&)[8], const float (&)[2][8]) const {}
 };
-// v <- fl(fl(v - T_perp[x]) - PosEmbed)
+// v <- fl(fl(v - T_perp[x]) - PosEmbed); TP / PE: which of the two tables exist (compile time, so that the
+// number of loads per tile is fixed).
+template <bool TP, bool PE>
 struct SubtractHighRank {
+    static constexpr int kTables = (TP ? 1 : 0) + (PE ? 1 : 0);
     HighRank h;
-    const float* tabs[2];        // this lane's T_perp row and positional row (one matrix row per lane)
-    // Called once per lane with the matrix row it stages: the token lookup leaves the K loop.
-    __device__ __forceinline__ void prepare(int row, int rows) {
-        tabs[0] = (h.t_perp && row < rows) ? h.perp_row(row) : nullptr;
-        tabs[1] = (h.pos && row < rows) ? h.pos_row(row) : nullptr;
+    const float* tabs[2];        // this lane's T_perp row and positional row: the token lookup leaves the K loop
+    __device__ __forceinline__ void prepare(int row) {
+        tabs[0] = TP ? h.perp_row(row) : nullptr;
+        tabs[1] = PE ? h.pos_row(row) : nullptr;
     }
-    __device__ __forceinline__ void operator()(int row, int col, int rows, int cols, float (&v)[8]) const {
-        if (row >= rows) return;
+    template <int F, bool GUARD>
+    __device__ __forceinline__ void fetch(int col, int cols, float (&t)[2][8]) const {
+        if (TP) row_load<F, GUARD>(tabs[0], col, cols, t[0]);
+        if (PE) row_load<F, GUARD>(tabs[1], col, cols, t[1]);
+    }
+    template <int F>
+    __device__ __forceinline__ void apply(float (&v)[8], const float (&t)[2][8]) const {
+        if (TP) {
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            if (!tabs[k]) continue;
-            float t[8];
-            load8(tabs[k], h.ld, 0, col, 1, cols, t);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = __fsub_rn(v[i], t[i]);
+            for (int i = 0; i < F; ++i) v[i] = __fsub_rn(v[i], t[0][i]);
         }
-    }
-    // the same for the first four values only (columns col .. col+3)
-    __device__ __forceinline__ void four(int row, int col, int rows, int cols, float (&v)[8]) const {
-        if (row >= rows) return;
+        if (PE) {
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            if (!tabs[k]) continue;
-            if (col + 4 <= cols) {
-                const vfloat4 t = ldg4(tabs[k] + col);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = __fsub_rn(v[i], t[i]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (col + i < cols) v[i] = __fsub_rn(v[i], tabs[k][col + i]);
-            }
+            for (int i = 0; i < F; ++i) v[i] = __fsub_rn(v[i], t[1][i]);
         }
     }
 };
@@ -206,8 +197,15 @@ struct AddHighRank {
 // B_NK = true: B is given as its transpose, row-major N x K (ldb), i.e. B[k][n] = Bt[n][k].
 // The A values pass through pro(row, col, M, K, values[8]) on their way in; the output goes
 // through epi(row, col, four values, N).
+// Waves per SIMD the register allocation must leave room for: the 128 x 128 tile holds 64 accumulator
+// registers, and a prologue with tables keeps up to 32 more values in flight per lane.
+template <int TM_, int TN_, class Pro>
+constexpr int gemm_min_waves() {
+    return (TM_ * TN_ == 128 * 128 ? 3 : 4) - (Pro::kTables > 0 ? 1 : 0);
+}
+
 template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
-__global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restrict__ A, int64_t lda,
+__global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void gemm_f32_kernel(const float* __restrict__ A, int64_t lda,
                                                             const float* __restrict__ B, int64_t ldb, int M, int N,
                                                             int K, Pro pro, Epi epi) {
     // TM_ x TN_ output tile; the four waves form a 2 x 2 grid, each with MI x NJ MFMA tiles of 32 x 32
@@ -235,54 +233,56 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
 
     // Staging assignment.  "Row-of-k" tiles (A always, B when given as N x K): a lane takes one matrix
     // row and AF (A) or BF (B) consecutive k.  "k-major" tiles (B as K x N): lane t takes k = t / 16 and
-    // BF consecutive n.
+    // BF consecutive n.  A lane whose row lies beyond the matrix stages the last row instead: it only
+    // feeds output rows (columns) that are never stored.
     const int ar = tid / (TK / AF), ak = (tid % (TK / AF)) * AF;
     const int br = tid / (TK / BF), bkk = (tid % (TK / BF)) * BF;
     const int bk = tid >> 4, bn = (tid & 15) * BF;
-    // Global loads run two K tiles ahead of the MFMAs (one tile of matrix work is shorter than the
-    // memory latency): tile t+2 is fetched into registers while tile t is multiplied and tile t+1,
-    // fetched one iteration earlier, waits in a second register set for its turn to go to LDS.
-    float ra[2][8], rb[2][8];
-    auto fetch = [&](int k0, float (&qa)[8], float (&qb)[8]) {
-        if (AF == 8) {
-            load8(A, lda, m0 + ar, k0 + ak, M, K, qa);
-            pro(m0 + ar, k0 + ak, M, K, qa);
-        } else {
-            load4(A, lda, m0 + ar, k0 + ak, M, K, qa);
-            pro.four(m0 + ar, k0 + ak, M, K, qa);
-        }
-        if (B_NK) {
-            if (BF == 8) load8(B, ldb, n0 + br, k0 + bkk, N, K, qb);
-            else load4(B, ldb, n0 + br, k0 + bkk, N, K, qb);
-        } else {
-            if (BF == 8) load8(B, ldb, k0 + bk, n0 + bn, K, N, qb);
-            else load4(B, ldb, k0 + bk, n0 + bn, K, N, qb);
-        }
-    };
-    auto stash = [&](int buf, const float (&qa)[8], const float (&qb)[8]) {
-#pragma unroll
-        for (int i = 0; i < AF; ++i) As[buf][ak + i][ar] = qa[i];
-        if (B_NK) {
-#pragma unroll
-            for (int i = 0; i < BF; ++i) Bs[buf][bkk + i][br] = qb[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < BF; ++i) Bs[buf][bk][bn + i] = qb[i];
-        }
-    };
+    const int arow = m0 + ar < M ? m0 + ar : M - 1;
+    const int brow = n0 + br < N ? n0 + br : N - 1;
+    const float* const pa = A + (int64_t)arow * lda;
+    // B as K x N: a lane whose BF columns lie wholly beyond N may read any columns instead (again: outputs
+    // that are never stored), so the plain loads also serve an edge column tile whenever no lane straddles N.
+    const int bcol = n0 + bn;
+    const bool bcol_inside = bcol + BF <= N;
+    const float* const pb = B_NK ? B + (int64_t)brow * ldb : B + (bcol_inside ? bcol : 0);
+    pro.prepare(arow);
 
-    const int n_tiles = (K + TK - 1) / TK;
-    pro.prepare(m0 + ar, M);
-    fetch(0, ra[0], rb[0]);
-    stash(0, ra[0], rb[0]);
-    if (n_tiles > 1) fetch(TK, ra[0], rb[0]);
-    __syncthreads();
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        if (t + 2 < n_tiles) fetch((t + 2) * TK, ra[1], rb[1]);
-        // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32].
-        // The operands of the next k pair are read from LDS before the MFMAs of the current pair are
-        // issued, so that the LDS latency hides behind the matrix pipe.
+    // One K tile on its way from global memory to LDS: raw A values, what the prologue combines with them, B.
+    struct Stage { float a[8], b[8], t[2][8]; };
+    Stage s0, s1;
+    // GUARD = false needs the whole K tile inside the matrix and, for B as K x N, no lane straddling column N.
+    auto fetch = [&](auto guard, int k0, Stage& q) {
+        constexpr bool GUARD = decltype(guard)::value;
+        row_load<AF, GUARD>(pa, k0 + ak, K, q.a);
+        pro.template fetch<AF, GUARD>(k0 + ak, K, q.t);
+        if (B_NK) {
+            row_load<BF, GUARD>(pb, k0 + bkk, K, q.b);
+        } else if (!GUARD) {
+            row_load<BF, false>(pb + (int64_t)(k0 + bk) * ldb, 0, BF, q.b);
+        } else {
+            // zeros beyond row K and beyond column N
+            const bool k_inside = k0 + bk < K;
+            row_load<BF, true>(B + (int64_t)(k_inside ? k0 + bk : 0) * ldb + (bcol < N ? bcol : 0), 0,
+                               k_inside ? N - bcol : 0, q.b);
+        }
+    };
+    auto stash = [&](int buf, Stage& q) {
+        pro.template apply<AF>(q.a, q.t);
+#pragma unroll
+        for (int i = 0; i < AF; ++i) As[buf][ak + i][ar] = q.a[i];
+        if (B_NK) {
+#pragma unroll
+            for (int i = 0; i < BF; ++i) Bs[buf][bkk + i][br] = q.b[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < BF; ++i) Bs[buf][bk][bn + i] = q.b[i];
+        }
+    };
+    // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32].
+    // The operands of the next k pair are read from LDS before the MFMAs of the current pair are
+    // issued, so that the LDS latency hides behind the matrix pipe.
+    auto multiply = [&](int buf) {
         const int kq = lane >> 5, rc = lane & 31;
         float fa[2][MI], fb[2][NJ];
         auto operands = [&](int kk, int st) {
@@ -304,9 +304,43 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(const float* __restr
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][i], fb[st][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (t + 1 < n_tiles) stash(buf ^ 1, ra[0], rb[0]);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { ra[0][i] = ra[1][i]; rb[0][i] = rb[1][i]; }
+    };
+
+    // Global loads run two K tiles ahead of the MFMAs (one tile of matrix work is shorter than the memory
+    // latency): tile t+2 is fetched into one register set while tile t is multiplied and tile t+1, fetched one
+    // iteration earlier, goes from the other set to LDS.  The leading n_fast tiles need no guard; their loop
+    // is branch-free between the barriers, which lets the wait before the LDS stores name the older tile
+    // alone.  What is left (a K tail, the last two tiles, every tile of a right-edge workgroup of a K x N
+    // operand whose N is not a multiple of BF) goes through the guarded loop.
+    const std::integral_constant<bool, false> plain;
+    const std::integral_constant<bool, true> guarded;
+    const int n_tiles = (K + TK - 1) / TK;
+    const int n_fast = (B_NK || n0 + TN_ <= N || N % BF == 0) ? K / TK : 0;
+    auto fetch_any = [&](int t, Stage& q) {
+        if (t < n_fast) fetch(plain, t * TK, q);
+        else fetch(guarded, t * TK, q);
+    };
+    fetch_any(0, s0);
+    stash(0, s0);
+    if (n_tiles > 1) fetch_any(1, s0);
+    __syncthreads();
+    int t = 0;
+    for (; t + 3 < n_fast; t += 2) {          // t is even here: tile t sits in LDS buffer 0
+        fetch(plain, (t + 2) * TK, s1);
+        multiply(0);
+        stash(1, s0);
+        __syncthreads();
+        fetch(plain, (t + 3) * TK, s0);
+        multiply(1);
+        stash(0, s1);
+        __syncthreads();
+    }
+    for (; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        if (t + 2 < n_tiles) fetch_any(t + 2, s1);
+        multiply(buf);
+        if (t + 1 < n_tiles) stash(buf ^ 1, s0);
+        s0 = s1;
         __syncthreads();
     }
 
@@ -790,8 +824,14 @@ extern "C" int sparseloco_subspace_project(const float* x, const float* t_perp, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (narrow_applies(d, k)) {
         launch_project_narrow(x, h, u, x_tilde, M, d, k, st);
-    } else if (t_perp || pos_embed)
-        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank{h, {nullptr, nullptr}},
+    } else if (t_perp && pos_embed)
+        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank<true, true>{h, {nullptr, nullptr}},
+                           StoreCoeff{x_tilde, (int64_t)k}, st);
+    else if (t_perp)
+        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank<true, false>{h, {nullptr, nullptr}},
+                           StoreCoeff{x_tilde, (int64_t)k}, st);
+    else if (pos_embed)
+        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank<false, true>{h, {nullptr, nullptr}},
                            StoreCoeff{x_tilde, (int64_t)k}, st);
     else
         launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{x_tilde, (int64_t)k}, st);
