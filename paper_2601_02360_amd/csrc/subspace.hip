@@ -752,21 +752,19 @@ void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, 
 //   columns: 64 wide when N spans an odd number of 64-column blocks (the last 128-wide tile would be at
 //            most half used), else 128 wide;
 //   rows:    128 when that still leaves two workgroups per compute unit, else 64;
-//   short_k_light_epilogue (the reconstruction: K = k, one store per output): 64-row tiles always and
-//            64 columns up to K = 192 -- with so short a K loop more, smaller workgroups per compute unit
-//            overlap one group's epilogue with another's products.
+//   a product with the basis as the N x K operand has K = k: up to K = 192 the K loop is so short that
+//            64 x 64 tiles win (more, smaller workgroups per compute unit overlap one group's epilogue
+//            with another's products); beyond that the reconstruction (light_epilogue: one store per
+//            output) still prefers 64 rows.
 template <bool B_NK, class Pro, class Epi>
 void launch_gemm(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
-                 hipStream_t st, bool short_k_light_epilogue = false) {
+                 hipStream_t st, bool light_epilogue = false) {
     auto groups = [&](int tm, int tn) { return (int64_t)((M + tm - 1) / tm) * ((N + tn - 1) / tn); };
     bool wide = ((N + 63) / 64) % 2 == 0;
     bool tall;
-    if (short_k_light_epilogue) {
-        wide = K > 192;
-        tall = false;
-    } else {
-        tall = groups(128, wide ? 128 : 64) >= 2 * 256;
-    }
+    if (B_NK && K <= 192) wide = tall = false;
+    else if (light_epilogue) tall = false;
+    else tall = groups(128, wide ? 128 : 64) >= 2 * 256;
     if (tall && wide) launch_gemm_tile<128, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
     else if (tall) launch_gemm_tile<128, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
     else if (wide) launch_gemm_tile<64, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
