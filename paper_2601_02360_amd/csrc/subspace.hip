@@ -13,10 +13,10 @@
 // inter-stage traffic of section 2.2:
 //     project      X~ = (X - T_perp[x] - PosEmbed) U        (also  grad_X U  with nothing subtracted)
 //     reconstruct  X^ = X~ U^T + T_perp[x] + PosEmbed
-// For a narrow basis (k <= 64, most of the subspace sizes the paper sweeps) these products are bound by
-// memory traffic, not by the matrix pipe, and two kernels of their own take over: project_narrow_kernel and
-// reconstruct_narrow_kernel (16 x 16 x 4 MFMAs, operands loaded from global memory directly in MFMA layout,
-// no barrier in the loop).
+// For a narrow basis (most of the subspace sizes the paper sweeps) these products are bound by memory
+// traffic, not by the matrix pipe.  The GEMM kernel's 64 x 64 tile handles that well; where it does not
+// (few or no tables to gather, small k), project_narrow_kernel takes over (16 x 16 x 4 MFMAs, operands
+// loaded from global memory directly in MFMA layout, no barrier in the loop).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -241,17 +241,18 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     const int arow = m0 + ar < M ? m0 + ar : M - 1;
     const int brow = n0 + br < N ? n0 + br : N - 1;
     const float* const pa = A + (int64_t)arow * lda;
-    // B as K x N: a lane whose BF columns lie wholly beyond N may read any columns instead (again: outputs
-    // that are never stored), so the plain loads also serve an edge column tile whenever no lane straddles N.
+    // B as K x N: columns at and beyond N only feed outputs that are never stored, so whatever is read for
+    // them will do.  A lane whose BF columns lie wholly beyond N reads columns 0 .. BF-1 instead; a lane that
+    // straddles N reads on into the next row of B, which exists for every K tile but the last few rows
+    // (see n_fast below).
     const int bcol = n0 + bn;
-    const bool bcol_inside = bcol + BF <= N;
-    const float* const pb = B_NK ? B + (int64_t)brow * ldb : B + (bcol_inside ? bcol : 0);
+    const float* const pb = B_NK ? B + (int64_t)brow * ldb : B + (bcol < N ? bcol : 0);
     pro.prepare(arow);
 
     // One K tile on its way from global memory to LDS: raw A values, what the prologue combines with them, B.
     struct Stage { float a[8], b[8], t[2][8]; };
     Stage s0, s1;
-    // GUARD = false needs the whole K tile inside the matrix and, for B as K x N, no lane straddling column N.
+    // GUARD = false needs the whole K tile inside the matrix (and, for B as K x N, spare rows behind it).
     auto fetch = [&](auto guard, int k0, Stage& q) {
         constexpr bool GUARD = decltype(guard)::value;
         row_load<AF, GUARD>(pa, k0 + ak, K, q.a);
@@ -310,12 +311,14 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     // latency): tile t+2 is fetched into one register set while tile t is multiplied and tile t+1, fetched one
     // iteration earlier, goes from the other set to LDS.  The leading n_fast tiles need no guard; their loop
     // is branch-free between the barriers, which lets the wait before the LDS stores name the older tile
-    // alone.  What is left (a K tail, the last two tiles, every tile of a right-edge workgroup of a K x N
-    // operand whose N is not a multiple of BF) goes through the guarded loop.
+    // alone.  What is left (a K tail, the last two tiles) goes through the guarded loop.
     const std::integral_constant<bool, false> plain;
     const std::integral_constant<bool, true> guarded;
     const int n_tiles = (K + TK - 1) / TK;
-    const int n_fast = (B_NK || n0 + TN_ <= N || N % BF == 0) ? K / TK : 0;
+    // Rows of B that must follow a tile for the reads past column N to stay inside the array (none if no lane
+    // straddles N: then every 16-byte read lies inside its row).
+    const int64_t spare_rows = (B_NK || n0 + TN_ <= N || N % BF == 0) ? 0 : (BF - 1 + ldb - 1) / ldb;
+    const int n_fast = K >= spare_rows ? (int)((K - spare_rows) / TK) : 0;
     auto fetch_any = [&](int t, Stage& q) {
         if (t < n_fast) fetch(plain, t * TK, q);
         else fetch(guarded, t * TK, q);
@@ -377,8 +380,8 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     }
 }
 
-// Projection onto a narrow basis: out[rows, k] = (x - T_perp[token] - PosEmbed) U with k <= 16 * NB <= 64
-// (section 2.2; the subspace dimensions the paper sweeps are d/8 ... d/768, so most of them land here).
+// Projection onto a narrow basis: out[rows, k] = (x - T_perp[token] - PosEmbed) U with k <= 16 * NB
+// (section 2.2; the subspace dimensions the paper sweeps go down to d/768).  Instantiated for NB = 1, 2.
 // With so few output columns the product is bound by reading x (and the gathered table rows) once, not
 // by the matrix pipe, and the wide GEMM tile above would spend most of its MFMAs on columns that do not
 // exist.  So: v_mfma_f32_16x16x4_f32, one workgroup per 16 rows, and the four waves split the reduction
@@ -567,15 +570,10 @@ template <bool TP, bool PE>
 void launch_project_narrow_tables(const float* x, const HighRank& h, const float* u, float* out, int rows, int d,
                                   int k, hipStream_t st) {
     const dim3 grid((unsigned)((rows + 15) / 16)), block(kThreads);
-    const int nb = (k + 15) / 16;
-    if (nb == 1)
+    if (k <= 16)
         hipLaunchKernelGGL((project_narrow_kernel<1, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
-    else if (nb == 2)
-        hipLaunchKernelGGL((project_narrow_kernel<2, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
-    else if (nb == 3)
-        hipLaunchKernelGGL((project_narrow_kernel<3, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
     else
-        hipLaunchKernelGGL((project_narrow_kernel<4, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
+        hipLaunchKernelGGL((project_narrow_kernel<2, 2, TP, PE>), grid, block, 0, st, x, h, u, out, rows, d, k);
 }
 void launch_project_narrow(const float* x, const HighRank& h, const float* u, float* out, int rows, int d, int k,
                            hipStream_t st) {
@@ -584,162 +582,13 @@ void launch_project_narrow(const float* x, const HighRank& h, const float* u, fl
     else if (h.pos) launch_project_narrow_tables<false, true>(x, h, u, out, rows, d, k, st);
     else launch_project_narrow_tables<false, false>(x, h, u, out, rows, d, k, st);
 }
-// Reconstruction from a narrow basis: out[rows, d] = x_tilde U^T + T_perp[token] + PosEmbed with k <= 16 Q <= 32.
-// The mirror image of the kernel above, and simpler: the product is computed transposed, D = U_block x_tilde^T,
-// so that the MFMA result layout (register v of lane (g, c) = element (4g + v, c) of D) hands every lane four
-// CONSECUTIVE d positions 4g .. 4g + 3 of row c of the output -- the same 16-byte pieces in which the table
-// rows are loaded and the result is stored.  The four waves take different 32-wide d tiles (w, w + 4, ...),
-// so there is nothing to reduce, no LDS and no barrier: U comes from L2 straight into the A operand
-// (lane (g, c): U[d0 + c][16 q + 4g .. + 3], the same permutation of k within a group of sixteen as above),
-// and the x_tilde values of the workgroup's 16 rows sit in registers as the B operand for the whole kernel.
-// Rows past the end repeat the last row and store the same values to it a second time.
-// VEC: k is a multiple of 4, so a lane's four k are either all inside the basis or all outside; otherwise
-// they are loaded one by one.  Positions outside the basis read some valid U value instead and meet a zero
-// of x_tilde.
-// EPI selects what happens to the product v = x_tilde U^T: EPI_ADD_* store fl(fl(v + T_perp[token]) + PosEmbed)
-// with either table optional (section 2.2); EPI_UPDATE is the second pass of the embedding re-projection
-// (section 2.4) on out = T_S and its companion T_perp, both in place: T_perp += T_S - v, T_S = v.  Every
-// element is read and written by the one lane that owns it (twice with identical values for a repeated row).
-enum { EPI_ADD_NONE = 0, EPI_ADD_PERP = 1, EPI_ADD_POS = 2, EPI_ADD_BOTH = 3, EPI_UPDATE = 4 };
-template <int Q, bool VEC, int EPI>
-__global__ __launch_bounds__(kThreads) void reconstruct_narrow_kernel(const float* __restrict__ xt, HighRank h,
-                                                                       const float* __restrict__ u, float* out,
-                                                                       float* t_perp_inout, int rows, int d, int k) {
-    constexpr bool TP = EPI == EPI_ADD_PERP || EPI == EPI_ADD_BOTH || EPI == EPI_UPDATE;   // first table tile loaded
-    constexpr bool PE = EPI == EPI_ADD_POS || EPI == EPI_ADD_BOTH || EPI == EPI_UPDATE;    // second table tile loaded
-    typedef float v4f __attribute__((ext_vector_type(4)));
-    constexpr int DT = 32;                       // d positions per tile: one 128-byte line of every output row
-    constexpr int PD = 2;                        // tiles in flight per wave
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = lane >> 4, c = lane & 15;
-    const int r = blockIdx.x * 16 + c;
-    const int row = r < rows ? r : rows - 1;
-    float* const po = out + (int64_t)row * d + 4 * g;
-    float* const po2 = EPI == EPI_UPDATE ? t_perp_inout + (int64_t)row * d + 4 * g : nullptr;
-    // the two table tiles of a stage: T_perp[token] and PosEmbed, or (update) the old T_S and T_perp
-    const float* const pt = EPI == EPI_UPDATE ? po : (TP ? h.perp_row(row) + 4 * g : nullptr);
-    const float* const pp = EPI == EPI_UPDATE ? po2 : (PE ? h.pos_row(row) + 4 * g : nullptr);
-
-    // k offsets of this lane within each group of sixteen, pulled back to 0 where they leave the basis
-    int koff[Q];
-    bool kin[Q][4];
-    float bx[Q][4];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int k0 = 16 * q + 4 * g;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            kin[q][s] = k0 + s < k;
-            bx[q][s] = kin[q][s] ? xt[(int64_t)row * k + k0 + s] : 0.f;
-        }
-        koff[q] = kin[q][0] ? k0 : 0;
-    }
-    const float* const pu = u + (int64_t)c * k;                   // row c of a 16-row block of U
-
-    struct Stage { vfloat4 u[2][Q], t[2], p[2]; };
-    Stage st[PD];
-    auto fetch = [&](int t, Stage& sg) {
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            const int d0 = t * DT + 16 * hh;
-            const float* ub = pu + (int64_t)d0 * k;
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                if (VEC) {
-                    sg.u[hh][q] = ldg4(ub + koff[q]);
-                } else {
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) sg.u[hh][q][s] = ub[kin[q][s] ? koff[q] + s : 0];
-                }
-            }
-            if (TP) sg.t[hh] = ldg4(pt + d0);
-            if (PE) sg.p[hh] = ldg4(pp + d0);
-        }
-    };
-    auto finish = [&](int t, const Stage& sg) {
-        v4f acc[2];
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) acc[hh] = v4f{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int q = 0; q < Q; ++q)
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh)
-                    acc[hh] = __builtin_amdgcn_mfma_f32_16x16x4f32(sg.u[hh][q][s], bx[q][s], acc[hh], 0, 0, 0);
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            vfloat4 v = {acc[hh][0], acc[hh][1], acc[hh][2], acc[hh][3]};
-            if (EPI == EPI_UPDATE) {
-                vfloat4 q;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) q[i] = __fadd_rn(sg.p[hh][i], __fsub_rn(sg.t[hh][i], v[i]));
-                stg4(po2 + t * DT + 16 * hh, q);
-            } else {
-                if (TP) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], sg.t[hh][i]);
-                }
-                if (PE) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], sg.p[hh][i]);
-                }
-            }
-            stg4(po + t * DT + 16 * hh, v);
-        }
-    };
-
-    // Wave w owns the n_mine tiles w, w + 4, ...  Loads are issued unconditionally (past the end the last tile
-    // is simply loaded again), so that the number in flight is known at every wait.
-    const int n_tiles = d / DT;
-    const int n_mine = wave < n_tiles ? (n_tiles - wave + 3) >> 2 : 0;
-    const int t_last = wave + 4 * (n_mine - 1);
-    auto tile = [&](int i) { const int t = wave + 4 * i; return t < t_last ? t : t_last; };
-    if (n_mine > 0) {
-#pragma unroll
-        for (int j = 0; j < PD; ++j) fetch(tile(j), st[j]);
-        int i = 0;
-        for (; i + PD <= n_mine; i += PD) {
-#pragma unroll
-            for (int j = 0; j < PD; ++j) {
-                finish(wave + 4 * (i + j), st[j]);
-                fetch(tile(i + j + PD), st[j]);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < PD - 1; ++j)
-            if (i + j < n_mine) finish(wave + 4 * (i + j), st[j]);
-    }
+// Where the narrow projection beats the GEMM kernel's 64 x 64 tile (measured at d 1536 / 2048, 16384 and 32000
+// rows): whole 32-wide d tiles, and at most 32 columns with at most one table to gather, or at most 16 with
+// both.  The more there is to gather per row, the less the narrow kernel's higher occupancy buys.
+bool narrow_applies(int d, int k, const HighRank& h) {
+    const int tables = (h.t_perp ? 1 : 0) + (h.pos ? 1 : 0);
+    return d % 32 == 0 && k <= (tables == 2 ? 16 : 32);
 }
-
-template <int Q, bool VEC>
-void launch_reconstruct_narrow_q(const float* xt, const HighRank& h, const float* u, float* out, float* t_perp_inout,
-                                 int rows, int d, int k, hipStream_t st) {
-    const dim3 grid((unsigned)((rows + 15) / 16)), block(kThreads);
-#define SPLC_LAUNCH_EPI(E)                                                                                       \
-    hipLaunchKernelGGL((reconstruct_narrow_kernel<Q, VEC, E>), grid, block, 0, st, xt, h, u, out, t_perp_inout, \
-                       rows, d, k)
-    if (t_perp_inout) SPLC_LAUNCH_EPI(EPI_UPDATE);
-    else if (h.t_perp && h.pos) SPLC_LAUNCH_EPI(EPI_ADD_BOTH);
-    else if (h.t_perp) SPLC_LAUNCH_EPI(EPI_ADD_PERP);
-    else if (h.pos) SPLC_LAUNCH_EPI(EPI_ADD_POS);
-    else SPLC_LAUNCH_EPI(EPI_ADD_NONE);
-#undef SPLC_LAUNCH_EPI
-}
-// t_perp_inout != nullptr selects the re-projection update on (out = T_S, t_perp_inout = T_perp).
-void launch_reconstruct_narrow(const float* xt, const HighRank& h, const float* u, float* out, float* t_perp_inout,
-                               int rows, int d, int k, hipStream_t st) {
-    if (k % 4 != 0) launch_reconstruct_narrow_q<1, false>(xt, h, u, out, t_perp_inout, rows, d, k, st);
-    else if (k <= 16) launch_reconstruct_narrow_q<1, true>(xt, h, u, out, t_perp_inout, rows, d, k, st);
-    else launch_reconstruct_narrow_q<2, true>(xt, h, u, out, t_perp_inout, rows, d, k, st);
-}
-// Where the narrow reconstruction beats the general kernel (measured): whole 32-wide d tiles and a basis of at
-// most 32 columns in multiples of four, or any basis of at most 8 columns.
-bool narrow_reconstruct_applies(int d, int k) { return d % 32 == 0 && ((k % 4 == 0 && k <= 32) || k <= 8); }
-
-// The narrow projection takes bases of at most 64 columns over a whole number of 32-wide d tiles.
-bool narrow_applies(int d, int k) { return k <= 64 && d % 32 == 0; }
 
 template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
 void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
@@ -784,17 +633,13 @@ extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const f
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int M = (int)vocab;
     // pass 1: coeff = T_S U            (M x k) = (M x d)(d x k)
-    if (narrow_applies(d, k))
+    if (narrow_applies(d, k, HighRank{nullptr, nullptr, 0, nullptr, 1, (int64_t)d}))
         launch_project_narrow(t_s, HighRank{nullptr, nullptr, 0, nullptr, 1, (int64_t)d}, u, coeff_ws, M, d, k, st);
     else
         launch_gemm<false>(t_s, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k}, st);
     // pass 2: Pi = coeff U^T           (M x d) = (M x k)(k x d), U given as d x k = the N x K form
-    if (narrow_reconstruct_applies(d, k))
-        launch_reconstruct_narrow(coeff_ws, HighRank{nullptr, nullptr, 0, nullptr, 1, (int64_t)d}, u, t_s, t_perp, M, d,
-                                  k, st);
-    else
-        launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{},
-                          UpdateEmbedding{t_s, t_perp, (int64_t)d}, st);
+    launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, UpdateEmbedding{t_s, t_perp, (int64_t)d},
+                      st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
@@ -820,7 +665,7 @@ extern "C" int sparseloco_subspace_project(const float* x, const float* t_perp, 
     const int M = (int)rows;
     const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (narrow_applies(d, k)) {
+    if (narrow_applies(d, k, h)) {
         launch_project_narrow(x, h, u, x_tilde, M, d, k, st);
     } else if (t_perp && pos_embed)
         launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank<true, true>{h, {nullptr, nullptr}},
@@ -848,9 +693,6 @@ extern "C" int sparseloco_subspace_reconstruct(const float* x_tilde, const float
     const int M = (int)rows;
     const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (narrow_reconstruct_applies(d, k))
-        launch_reconstruct_narrow(x_tilde, h, u, x_hat, nullptr, M, d, k, st);
-    else
-        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat}, st, true);
+    launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat}, st, true);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }

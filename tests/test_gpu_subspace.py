@@ -87,15 +87,20 @@ def test_argument_checks():
 @pytest.mark.parametrize("rows,seq,d,k,vocab,use_perp,use_pos", [
     (256, 64, 128, 16, 50, True, True), (300, 100, 200, 7, 33, True, True), (129, 43, 130, 130, 5, True, False),
     (512, 128, 768, 96, 1000, False, True), (1000, 250, 1536, 2, 64, True, True), (640, 64, 2048, 256, 512, False, False),
-    # bases of at most 64 columns take the narrow kernel: every column-block count, reduction lengths that
-    # leave some of a workgroup's waves without a tile or end inside a tile, row counts off the 16-row grid
+    # narrow bases (the narrow kernel up to 32 columns, or 16 with both tables; the 64 x 64 GEMM tile otherwise):
+    # reduction lengths that leave some of a workgroup's waves without a tile or end inside a tile, row counts
+    # off the 16-row grid
     (257, 64, 100, 33, 20, True, False), (64, 16, 36, 36, 7, False, True), (1000, 128, 512, 64, 100, True, True),
     (33, 33, 70, 48, 9, True, True), (500, 50, 2048, 17, 30, False, False), (16, 16, 1, 1, 3, True, True),
     (4099, 1024, 1536, 8, 3000, True, True), (15, 5, 257, 64, 4, False, False), (2048, 512, 768, 32, 500, False, True),
-    # the narrow reconstruction: k in fours up to 32, or any k up to 8 loaded one by one; single rows and tiles
+    # more narrow bases, single rows and single tiles
     (77, 11, 64, 3, 9, True, False), (200, 40, 96, 5, 50, False, False), (333, 37, 256, 24, 100, True, True),
     (50, 50, 32, 12, 5, False, True), (1, 1, 32, 4, 2, True, True), (130, 13, 160, 1, 7, True, True),
-    (1000, 100, 1024, 20, 300, True, False)])
+    (1000, 100, 1024, 20, 300, True, False),
+    # the GEMM kernel with a basis whose width is no multiple of four: its loads run past column k into the next
+    # row of U, except in the guarded last tiles
+    (700, 70, 512, 42, 60, True, True), (300, 30, 1024, 21, 10, True, True), (90, 9, 64, 63, 5, False, True),
+    (64, 8, 48, 1, 3, True, True), (2000, 200, 2048, 170, 100, True, False)])
 def test_project_and_reconstruct_match_the_oracle(rows, seq, d, k, vocab, use_perp, use_pos):
     rng = np.random.default_rng(rows + d + k)
     u64 = subspace.orthonormal_basis(d, k, rows)
