@@ -410,6 +410,22 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    # Reference point for the roofline fraction (outside the timed region): what a plain library kernel with
+    # the compress kernel's access pattern -- three streamed reads, one streamed write -- reaches on this machine.
+    ref = [torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_() for _ in range(4)]
+    for _ in range(3):
+        torch.addcmul(ref[0], ref[1], ref[2], value=0.5, out=ref[3])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        torch.addcmul(ref[0], ref[1], ref[2], value=0.5, out=ref[3])
+    e1.record()
+    torch.cuda.synchronize()
+    stream_ref_gbs = 10 * 16.0 * (1 << 28) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del ref
+    print("reference: torch.addcmul over 1 GiB arrays (3 reads + 1 write) streams %.0f GB/s on this box"
+          % stream_ref_gbs, file=sys.stderr, flush=True)
+
     ms_step = 1e3 * elapsed / args.steps
     n = rs.num_params
     nch = plan.num_chunks
@@ -453,6 +469,7 @@ def main():
                    "step_algorithmic_bytes": total_bytes,
                    "step_frac_of_hbm_peak": gbs(total_bytes, ms_step) / HBM_PEAK_GBS,
                    "kernel_ms": {"compress": avg(ms_c), "aggregate": avg(ms_a), "outer_update": avg(ms_u)},
+                   "stream_reference_gbs": stream_ref_gbs,
                    "fused_line5_ms_per_step": ms_fused, "fused_line5_params_per_s": n / (ms_fused * 1e-3),
                    "batched_ms_per_step": ms_batched,
                    "batched_params_per_s": None if ms_batched is None else n / (ms_batched * 1e-3),
