@@ -59,13 +59,20 @@ __device__ __forceinline__ void row_load(const float* __restrict__ row, int col,
 }
 
 
-// Epilogues receive four consecutive columns of one output row (col is a multiple of 4; columns
-// at or beyond n_cols do not exist).
+// Epilogues receive four consecutive columns of one output row (col is a multiple of 4).  Two forms:
+// operator() for a tile on the edge of the output (columns at or beyond n_cols do not exist), and, for a
+// tile that lies wholly inside, load() + store(): the kernel issues the loads of all its pieces of a
+// 32-row slab before the slab goes through LDS, so that their latency hides behind that round trip
+// instead of being paid piece by piece.
 
 // Pass 1: store the coefficients.
 struct StoreCoeff {
     float* c;
     int64_t ld;
+    __device__ __forceinline__ void load(int, int, vfloat4 (&)[2]) const {}
+    __device__ __forceinline__ void store(int row, int col, vfloat4 v, const vfloat4 (&)[2]) const {
+        stg4(c + (int64_t)row * ld + col, v);
+    }
     __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
         float* p = c + (int64_t)row * ld + col;
         if (col + 4 <= n_cols) {
@@ -83,6 +90,19 @@ struct UpdateEmbedding {
     float* t_s;
     float* t_perp;
     int64_t ld;
+    __device__ __forceinline__ void load(int row, int col, vfloat4 (&r)[2]) const {
+        const int64_t at = (int64_t)row * ld + col;
+        r[0] = ldg4(t_s + at);
+        r[1] = ldg4(t_perp + at);
+    }
+    __device__ __forceinline__ void store(int row, int col, vfloat4 v, const vfloat4 (&r)[2]) const {
+        const int64_t at = (int64_t)row * ld + col;
+        vfloat4 q;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) q[i] = __fadd_rn(r[1][i], __fsub_rn(r[0][i], v[i]));
+        stg4(t_perp + at, q);
+        stg4(t_s + at, v);
+    }
     __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
         const int64_t at = (int64_t)row * ld + col;
         if (col + 4 <= n_cols) {
@@ -162,32 +182,40 @@ struct SubtractHighRank {
     }
 };
 
-// Epilogue of reconstruct: out <- fl(fl(v + T_perp[x]) + PosEmbed)
+// Epilogue of reconstruct: out <- fl(fl(v + T_perp[x]) + PosEmbed); TP / PE: which tables exist.
+template <bool TP, bool PE>
 struct AddHighRank {
     HighRank h;
     float* out;
+    __device__ __forceinline__ void load(int row, int col, vfloat4 (&r)[2]) const {
+        if (TP) r[0] = ldg4(h.perp_row(row) + col);
+        if (PE) r[1] = ldg4(h.pos_row(row) + col);
+    }
+    __device__ __forceinline__ void store(int row, int col, vfloat4 v, const vfloat4 (&r)[2]) const {
+        if (TP) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], r[0][i]);
+        }
+        if (PE) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], r[1][i]);
+        }
+        stg4(out + (int64_t)row * h.ld + col, v);
+    }
     __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
-        float* p = out + (int64_t)row * h.ld + col;
         if (col + 4 <= n_cols) {
-            if (h.t_perp) {
-                const vfloat4 t = ldg4(h.perp_row(row) + col);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], t[i]);
-            }
-            if (h.pos) {
-                const vfloat4 t = ldg4(h.pos_row(row) + col);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], t[i]);
-            }
-            stg4(p, v);
+            vfloat4 r[2];
+            load(row, col, r);
+            store(row, col, v, r);
         } else {
+            float* p = out + (int64_t)row * h.ld + col;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 if (col + i < n_cols) {
-                    float r = v[i];
-                    if (h.t_perp) r = __fadd_rn(r, h.perp_row(row)[col + i]);
-                    if (h.pos) r = __fadd_rn(r, h.pos_row(row)[col + i]);
-                    p[i] = r;
+                    float x = v[i];
+                    if (TP) x = __fadd_rn(x, h.perp_row(row)[col + i]);
+                    if (PE) x = __fadd_rn(x, h.pos_row(row)[col + i]);
+                    p[i] = x;
                 }
         }
     }
@@ -353,6 +381,7 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     // buffers (same size); the K loop ended with a barrier, so they are free.
     float* slab = &Bs[0][0][0];
     static_assert(2 * TK * PB >= 32 * PB, "slab must fit the B staging buffers");
+    const bool inside = m0 + TM_ <= M && n0 + TN_ <= N;      // the whole output tile exists
 #pragma unroll
     for (int s = 0; s < TM_ / 32; ++s) {
         if (wm == s / MI) {
@@ -363,18 +392,26 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
                     slab[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * PB + wn * (32 * NJ) + j * 32 + (lane & 31)] =
                         acc[s % MI][j][v];
         }
-        __syncthreads();
         constexpr int VPR = TN_ / 4;                // 16-byte pieces per slab row
+        constexpr int NQ = 32 * VPR / kThreads;     // pieces per lane
+        vfloat4 held[NQ][2];
+        if (inside) {
 #pragma unroll
-        for (int q = 0; q < 32 * VPR / kThreads; ++q) {
+            for (int q = 0; q < NQ; ++q) {
+                const int f = tid + kThreads * q;
+                epi.load(m0 + 32 * s + f / VPR, n0 + (f % VPR) * 4, held[q]);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
             const int f = tid + kThreads * q;
             const int r = f / VPR, c4 = (f % VPR) * 4;
             const int row = m0 + 32 * s + r, col = n0 + c4;
-            if (row < M && col < N) {
-                const float* src = slab + r * PB + c4;
-                vfloat4 v = {src[0], src[1], src[2], src[3]};
-                epi(row, col, v, N);
-            }
+            const float* src = slab + r * PB + c4;
+            const vfloat4 v = {src[0], src[1], src[2], src[3]};
+            if (inside) epi.store(row, col, v, held[q]);
+            else if (row < M && col < N) epi(row, col, v, N);
         }
         __syncthreads();
     }
@@ -693,6 +730,17 @@ extern "C" int sparseloco_subspace_reconstruct(const float* x_tilde, const float
     const int M = (int)rows;
     const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
     hipStream_t st = static_cast<hipStream_t>(stream);
-    launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank{h, x_hat}, st, true);
+    if (t_perp && pos_embed)
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<true, true>{h, x_hat}, st,
+                          true);
+    else if (t_perp)
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<true, false>{h, x_hat}, st,
+                          true);
+    else if (pos_embed)
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<false, true>{h, x_hat}, st,
+                          true);
+    else
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<false, false>{h, x_hat},
+                          st, true);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
