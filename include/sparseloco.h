@@ -196,6 +196,26 @@ int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas,
                                 int n_reset, float* const* const* theta_local_reset, void* stream);
 
 /*
+ * How the dense products of the three entry points below (sections 2.2 and 2.4;
+ * the paper fixes no precision for them) are formed on the matrix cores.
+ * Process-wide; takes effect for calls made after it returns.
+ *   SPLC_MATMUL_FP32    (default) fp32 MFMA on the fp32 operands.
+ *   SPLC_MATMUL_BF16X3  every fp32 operand is split exactly into three bf16
+ *                       pieces and a product is the sum of the six piece
+ *                       products of leading order on the bf16 MFMA (16 times
+ *                       the fp32 rate), accumulated in fp32.  Each piece
+ *                       product is exact in fp32; what is dropped is below
+ *                       2^-23 |x y| per product, the size of an fp32 rounding
+ *                       step.  Operands must be finite and normal-or-zero.
+ * Bases of at most 32 columns (16 with both tables of section 2.2), where the
+ * product is bound by memory traffic, always use fp32.
+ * sparseloco_set_matmul_mode returns SPLC_EINVAL for another value.
+ */
+enum { SPLC_MATMUL_FP32 = 0, SPLC_MATMUL_BF16X3 = 1 };
+int sparseloco_set_matmul_mode(int mode);
+int sparseloco_get_matmul_mode(void);
+
+/*
  * Section 2.4 ("Token Embeddings and Heterogeneous Setting"): after every outer
  * synchronisation the embedding component T_S is projected back onto the
  * compression subspace S = Col(U) and the part the projection removes is

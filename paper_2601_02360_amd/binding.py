@@ -23,6 +23,7 @@ SPLC_DELTA_FROM_PARAMS, SPLC_DELTA_DIRECT = 0, 1
 SPLC_QUANT_NONE, SPLC_QUANT_2BIT = 0, 1
 SPLC_SELECT_AUTO, SPLC_SELECT_RADIX = 0, 1
 SPLC_LAYOUT_FLAT, SPLC_LAYOUT_TILE64 = 0, 1
+SPLC_MATMUL_FP32, SPLC_MATMUL_BF16X3 = 0, 1
 
 EXPORTS = [
     "sparseloco_plan_create", "sparseloco_plan_create_2d", "sparseloco_plan_destroy", "sparseloco_plan_num_chunks",
@@ -31,7 +32,7 @@ EXPORTS = [
     "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
     "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
     "sparseloco_reproject_embedding", "sparseloco_subspace_project", "sparseloco_subspace_reconstruct",
-    "sparseloco_strerror",
+    "sparseloco_set_matmul_mode", "sparseloco_get_matmul_mode", "sparseloco_strerror",
 ]
 
 _lib = None
@@ -70,6 +71,10 @@ def lib():
         L.sparseloco_plan_quant_mode.argtypes = [vp]
         L.sparseloco_plan_set_select.restype = i32
         L.sparseloco_plan_set_select.argtypes = [vp, i32]
+        L.sparseloco_set_matmul_mode.restype = i32
+        L.sparseloco_set_matmul_mode.argtypes = [i32]
+        L.sparseloco_get_matmul_mode.restype = i32
+        L.sparseloco_get_matmul_mode.argtypes = []
         L.sparseloco_compress.restype = i32
         L.sparseloco_compress.argtypes = [vp, i32, i32, pp, pp, pp, f32, vp, vp, vp]
         L.sparseloco_aggregate.restype = i32
@@ -268,6 +273,17 @@ def sparseloco_reproject_embedding(t_s: torch.Tensor, t_perp: torch.Tensor, u: t
                                               int(vocab), int(d), int(k), _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_reproject_embedding")
+
+
+def sparseloco_set_matmul_mode(mode: int) -> None:
+    """SPLC_MATMUL_FP32 (default) or SPLC_MATMUL_BF16X3 for the dense products of the three calls around here."""
+    rc = lib().sparseloco_set_matmul_mode(int(mode))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_set_matmul_mode")
+
+
+def sparseloco_get_matmul_mode() -> int:
+    return int(lib().sparseloco_get_matmul_mode())
 
 
 def _opt(t):

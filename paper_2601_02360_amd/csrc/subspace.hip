@@ -30,6 +30,32 @@ constexpr int TM = 128, TK = 16;         // largest M tile (bounds the row count
 constexpr int kThreads = 256;
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t vuint4 __attribute__((ext_vector_type(4)));
+typedef uint32_t vuint2 __attribute__((ext_vector_type(2)));
+
+// How the fp32 products are formed.
+//   MATH_F32:    v_mfma_f32_32x32x2_f32 on the operands as they are.
+//   MATH_BF16X3: every fp32 operand is split exactly into three bf16 pieces, x = x0 + x1 + x2 (8 mantissa
+//                bits each), and a product is the sum of the six piece products x_i y_j with i + j <= 2 on
+//                v_mfma_f32_32x32x16_bf16, accumulated in fp32.  A piece product is exact in fp32; the three
+//                dropped terms are below 2^-23 |x y|, the size of an fp32 rounding step.  The bf16 matrix
+//                pipe is 16 times as fast as the fp32 one, so six products still cost less than half of one
+//                fp32 product.
+enum { MATH_F32 = 0, MATH_BF16X3 = 1 };
+
+// The three bf16 pieces of x as bit patterns in the upper halves of h[0..2] (truncating splits: every
+// subtraction is exact, and x == h0 + h1 + h2 exactly for a normal fp32 x).
+__device__ __forceinline__ void split3(float x, uint32_t (&h)[3]) {
+    h[0] = __float_as_uint(x) & 0xFFFF0000u;
+    const float r1 = __fsub_rn(x, __uint_as_float(h[0]));
+    h[1] = __float_as_uint(r1) & 0xFFFF0000u;
+    h[2] = __float_as_uint(__fsub_rn(r1, __uint_as_float(h[1])));
+}
+// Two bf16 values (upper halves of lo and hi) as one dword, lo in the lower half.
+__device__ __forceinline__ uint32_t pack_bf16(uint32_t lo, uint32_t hi) {
+    return __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+}
 typedef float vfloat4 __attribute__((ext_vector_type(4), aligned(4)));
 #define SPLC_GLOBAL __attribute__((address_space(1)))
 
@@ -227,24 +253,43 @@ struct AddHighRank {
 // through epi(row, col, four values, N).
 // Waves per SIMD the register allocation must leave room for: the 128 x 128 tile holds 64 accumulator
 // registers, and a prologue with tables keeps up to 32 more values in flight per lane.
-template <int TM_, int TN_, class Pro>
+template <int MATH, int TM_, int TN_, class Pro>
 constexpr int gemm_min_waves() {
-    return (TM_ * TN_ == 128 * 128 ? 3 : 4) - (Pro::kTables > 0 ? 1 : 0);
+    return (TM_ * TN_ == 128 * 128 ? 3 : 4) - (Pro::kTables > 0 ? 1 : 0) - (MATH == MATH_BF16X3 ? 1 : 0);
 }
 
-template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
-__global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void gemm_f32_kernel(const float* __restrict__ A, int64_t lda,
-                                                            const float* __restrict__ B, int64_t ldb, int M, int N,
-                                                            int K, Pro pro, Epi epi) {
+// Staging buffers of one workgroup, two K tiles deep.
+//   MATH_F32:    k-major fp32 tiles with a padded pitch (operands are read one float per lane).
+//   MATH_BF16X3: per operand three planes (one per bf16 piece) of rows of 16 k = 32 bytes; a lane reads the 16
+//                bytes of one half row, and the halves of rows 8..15 (mod 16) are swapped so that sixteen
+//                consecutive rows cover all LDS banks.
+template <int MATH, int TM_, int TN_>
+struct GemmStaging;
+template <int TM_, int TN_>
+struct GemmStaging<MATH_F32, TM_, TN_> {
+    float a[2][TK][TM_ + 4];
+    float b[2][TK][TN_ + 4];
+};
+template <int TM_, int TN_>
+struct GemmStaging<MATH_BF16X3, TM_, TN_> {
+    uint32_t a[2][3][TM_][8];
+    uint32_t b[2][3][TN_][8];
+};
+
+template <int MATH, int TM_, int TN_, bool B_NK, class Pro, class Epi>
+__global__ __launch_bounds__(kThreads, (gemm_min_waves<MATH, TM_, TN_, Pro>())) void gemm_kernel(
+    const float* __restrict__ A, int64_t lda, const float* __restrict__ B, int64_t ldb, int M, int N, int K, Pro pro,
+    Epi epi) {
     // TM_ x TN_ output tile; the four waves form a 2 x 2 grid, each with MI x NJ MFMA tiles of 32 x 32
     // (128 x 128: 2 x 2 per wave; the smaller tiles give small problems more workgroups and waste less of
     // the last column tile when N is a multiple of 64 only).
     static_assert((TM_ == 128 || TM_ == 64) && (TN_ == 128 || TN_ == 64), "supported tiles");
+    constexpr bool SPLIT = MATH == MATH_BF16X3;
     constexpr int MI = TM_ / 64, NJ = TN_ / 64;
     constexpr int AF = TM_ / 16, BF = TN_ / 16;      // floats of the A / B tile per lane: 8 or 4
-    constexpr int PA = TM_ + 4, PB = TN_ + 4;        // LDS row pitches in floats
-    __shared__ float As[2][TK][PA];
-    __shared__ float Bs[2][TK][PB];
+    constexpr int PB = TN_ + 4;                      // row pitch of the epilogue slab (and of the fp32 B tile)
+    __shared__ __attribute__((aligned(16))) GemmStaging<MATH, TM_, TN_> sm;
+    static_assert(sizeof(sm.b) >= sizeof(float) * 32 * PB, "the epilogue slab reuses the B staging buffers");
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -263,8 +308,13 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     // row and AF (A) or BF (B) consecutive k.  "k-major" tiles (B as K x N): lane t takes k = t / 16 and
     // BF consecutive n.  A lane whose row lies beyond the matrix stages the last row instead: it only
     // feeds output rows (columns) that are never stored.
+    // With split operands every tile is staged row-of-k (the MFMA wants eight consecutive k per lane), so for B
+    // as K x N a lane then takes one column n = t % TN_ and loads its BF values of k one by one, each load
+    // coalesced across the lanes.
+    constexpr bool B_ROWS = B_NK || SPLIT;
     const int ar = tid / (TK / AF), ak = (tid % (TK / AF)) * AF;
-    const int br = tid / (TK / BF), bkk = (tid % (TK / BF)) * BF;
+    const int br = (SPLIT && !B_NK) ? tid % TN_ : tid / (TK / BF);
+    const int bkk = (SPLIT && !B_NK) ? (tid / TN_) * BF : (tid % (TK / BF)) * BF;
     const int bk = tid >> 4, bn = (tid & 15) * BF;
     const int arow = m0 + ar < M ? m0 + ar : M - 1;
     const int brow = n0 + br < N ? n0 + br : N - 1;
@@ -274,7 +324,7 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     // straddles N reads on into the next row of B, which exists for every K tile but the last few rows
     // (see n_fast below).
     const int bcol = n0 + bn;
-    const float* const pb = B_NK ? B + (int64_t)brow * ldb : B + (bcol < N ? bcol : 0);
+    const float* const pb = B_NK ? B + (int64_t)brow * ldb : (SPLIT ? B + brow : B + (bcol < N ? bcol : 0));
     pro.prepare(arow);
 
     // One K tile on its way from global memory to LDS: raw A values, what the prologue combines with them, B.
@@ -287,6 +337,12 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
         pro.template fetch<AF, GUARD>(k0 + ak, K, q.t);
         if (B_NK) {
             row_load<BF, GUARD>(pb, k0 + bkk, K, q.b);
+        } else if (SPLIT) {
+#pragma unroll
+            for (int i = 0; i < BF; ++i) {
+                const int kk = k0 + bkk + i;
+                q.b[i] = (!GUARD || kk < K) ? pb[(int64_t)(GUARD ? (kk < K ? kk : 0) : kk) * ldb] : 0.f;
+            }
         } else if (!GUARD) {
             row_load<BF, false>(pb + (int64_t)(k0 + bk) * ldb, 0, BF, q.b);
         } else {
@@ -296,29 +352,81 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
                                k_inside ? N - bcol : 0, q.b);
         }
     };
+    // F consecutive k (starting at k = kfirst, a multiple of F) of one tile row, split and stored plane by plane
+    auto stash_split = [&](uint32_t (*plane0)[8], int plane_rows, int row, int kfirst, const float (&v)[8], auto fcount) {
+        constexpr int F = decltype(fcount)::value;
+        uint32_t h[8][3];
+#pragma unroll
+        for (int i = 0; i < F; ++i) split3(v[i], h[i]);
+        const int half = (kfirst >> 3) ^ ((row >> 3) & 1);
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            uint32_t* dst = &plane0[p * plane_rows + row][4 * half + ((kfirst & 7) >> 1)];
+            if (F == 8)
+                *reinterpret_cast<vuint4*>(dst) = vuint4{pack_bf16(h[0][p], h[1][p]), pack_bf16(h[2][p], h[3][p]),
+                                                         pack_bf16(h[4][p], h[5][p]), pack_bf16(h[6][p], h[7][p])};
+            else
+                *reinterpret_cast<vuint2*>(dst) = vuint2{pack_bf16(h[0][p], h[1][p]), pack_bf16(h[2][p], h[3][p])};
+        }
+    };
     auto stash = [&](int buf, Stage& q) {
         pro.template apply<AF>(q.a, q.t);
-#pragma unroll
-        for (int i = 0; i < AF; ++i) As[buf][ak + i][ar] = q.a[i];
-        if (B_NK) {
-#pragma unroll
-            for (int i = 0; i < BF; ++i) Bs[buf][bkk + i][br] = q.b[i];
+        if constexpr (SPLIT) {
+            stash_split(&sm.a[buf][0][0], TM_, ar, ak, q.a, std::integral_constant<int, AF>{});
+            stash_split(&sm.b[buf][0][0], TN_, br, bkk, q.b, std::integral_constant<int, BF>{});
         } else {
 #pragma unroll
-            for (int i = 0; i < BF; ++i) Bs[buf][bk][bn + i] = q.b[i];
+            for (int i = 0; i < AF; ++i) sm.a[buf][ak + i][ar] = q.a[i];
+            if (B_NK) {
+#pragma unroll
+                for (int i = 0; i < BF; ++i) sm.b[buf][bkk + i][br] = q.b[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < BF; ++i) sm.b[buf][bk][bn + i] = q.b[i];
+            }
         }
     };
     // operand layout of v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32].
     // The operands of the next k pair are read from LDS before the MFMAs of the current pair are
     // issued, so that the LDS latency hides behind the matrix pipe.
+    // With split operands: v_mfma_f32_32x32x16_bf16 takes from lane l the eight k = 8 (l / 32) .. + 7 of row
+    // (column) l % 32 -- one 16-byte half row of a plane -- and one K tile is one such MFMA per piece pair.
     auto multiply = [&](int buf) {
         const int kq = lane >> 5, rc = lane & 31;
+        if constexpr (SPLIT) {
+            bf16x8 pa_[3][MI], pb_[3][NJ];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int row = wm * (32 * MI) + 32 * i + rc;
+                    pa_[p][i] = __builtin_bit_cast(
+                        bf16x8, *reinterpret_cast<const vuint4*>(&sm.a[buf][p][row][4 * (kq ^ ((row >> 3) & 1))]));
+                }
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const int row = wn * (32 * NJ) + 32 * j + rc;
+                    pb_[p][j] = __builtin_bit_cast(
+                        bf16x8, *reinterpret_cast<const vuint4*>(&sm.b[buf][p][row][4 * (kq ^ ((row >> 3) & 1))]));
+                }
+            }
+            // smallest terms first
+            constexpr int pairs[6][2] = {{2, 0}, {1, 1}, {0, 2}, {1, 0}, {0, 1}, {0, 0}};
+#pragma unroll
+            for (int c = 0; c < 6; ++c)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_[pairs[c][0]][i], pb_[pairs[c][1]][j],
+                                                                            acc[i][j], 0, 0, 0);
+        } else {
         float fa[2][MI], fb[2][NJ];
         auto operands = [&](int kk, int st) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i) fa[st][i] = As[buf][kk + kq][wm * (32 * MI) + 32 * i + rc];
+            for (int i = 0; i < MI; ++i) fa[st][i] = sm.a[buf][kk + kq][wm * (32 * MI) + 32 * i + rc];
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) fb[st][j] = Bs[buf][kk + kq][wn * (32 * NJ) + 32 * j + rc];
+            for (int j = 0; j < NJ; ++j) fb[st][j] = sm.b[buf][kk + kq][wn * (32 * NJ) + 32 * j + rc];
         };
         operands(0, 0);
 #pragma unroll
@@ -333,6 +441,7 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[st][i], fb[st][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
+        }
     };
 
     // Global loads run two K tiles ahead of the MFMAs (one tile of matrix work is shorter than the memory
@@ -345,7 +454,7 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     const int n_tiles = (K + TK - 1) / TK;
     // Rows of B that must follow a tile for the reads past column N to stay inside the array (none if no lane
     // straddles N: then every 16-byte read lies inside its row).
-    const int64_t spare_rows = (B_NK || n0 + TN_ <= N || N % BF == 0) ? 0 : (BF - 1 + ldb - 1) / ldb;
+    const int64_t spare_rows = (B_ROWS || n0 + TN_ <= N || N % BF == 0) ? 0 : (BF - 1 + ldb - 1) / ldb;
     const int n_fast = K >= spare_rows ? (int)((K - spare_rows) / TK) : 0;
     auto fetch_any = [&](int t, Stage& q) {
         if (t < n_fast) fetch(plain, t * TK, q);
@@ -379,8 +488,7 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<TM_, TN_, Pro>())) void g
     // (16 bytes per lane, 4 TN_ bytes per row) instead of the MFMA result layout, in which register v
     // of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32].  The slab reuses the B staging
     // buffers (same size); the K loop ended with a barrier, so they are free.
-    float* slab = &Bs[0][0][0];
-    static_assert(2 * TK * PB >= 32 * PB, "slab must fit the B staging buffers");
+    float* slab = reinterpret_cast<float*>(&sm.b);
     const bool inside = m0 + TM_ <= M && n0 + TN_ <= N;      // the whole output tile exists
 #pragma unroll
     for (int s = 0; s < TM_ / 32; ++s) {
@@ -627,12 +735,18 @@ bool narrow_applies(int d, int k, const HighRank& h) {
     return d % 32 == 0 && k <= (tables == 2 ? 16 : 32);
 }
 
+int g_matmul_mode = SPLC_MATMUL_FP32;      // process-wide, set by sparseloco_set_matmul_mode
+
 template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
 void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
                       hipStream_t st) {
     dim3 grid((unsigned)((N + TN_ - 1) / TN_), (unsigned)((M + TM_ - 1) / TM_));
-    hipLaunchKernelGGL((gemm_f32_kernel<TM_, TN_, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B, ldb, M, N,
-                       K, pro, epi);
+    if (g_matmul_mode == SPLC_MATMUL_BF16X3)
+        hipLaunchKernelGGL((gemm_kernel<MATH_BF16X3, TM_, TN_, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B,
+                           ldb, M, N, K, pro, epi);
+    else
+        hipLaunchKernelGGL((gemm_kernel<MATH_F32, TM_, TN_, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B,
+                           ldb, M, N, K, pro, epi);
 }
 // Tile choice (measured on the shapes of sections 2.2 and 2.4 at d 1536 / 2048, k = d/8 ... d/16):
 //   columns: 64 wide when N spans an odd number of 64-column blocks (the last 128-wide tile would be at
@@ -660,6 +774,14 @@ void launch_gemm(const float* A, int64_t lda, const float* B, int64_t ldb, int M
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
 
 }  // namespace
+
+extern "C" int sparseloco_set_matmul_mode(int mode) {
+    if (mode != SPLC_MATMUL_FP32 && mode != SPLC_MATMUL_BF16X3) return SPLC_EINVAL;
+    g_matmul_mode = mode;
+    return SPLC_OK;
+}
+
+extern "C" int sparseloco_get_matmul_mode(void) { return g_matmul_mode; }
 
 extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, float* coeff_ws,
                                               int64_t vocab, int d, int k, void* stream) {

@@ -6,6 +6,11 @@ sums modelled as independent, a dot product of length n has relative error about
 (eps = 2^-24) with respect to |x| |u|; the bar below is 8 (sqrt(d) + sqrt(k)) eps per ROW in the
 2-norm, relative to the row norm of T_S, for the projection, and the same plus one rounding of the
 sum for T_perp.  The worst-case bound (d + k) eps is also asserted element-wise.
+
+Every test runs twice: with fp32 MFMA products and with SPLC_MATMUL_BF16X3 (operands split exactly into three
+bf16 pieces, six piece products per product).  The split drops less than 3 * 2^-24 |x y| per product --
+part of a rounding step, far inside the bars above -- and products with an exact result (a coordinate
+subspace) stay exact, so both modes are held to the same bars.
 """
 import numpy as np
 import pytest
@@ -16,6 +21,14 @@ from paper_2601_02360_amd import binding as B
 
 pytestmark = pytest.mark.gpu
 EPS = 2.0 ** -24
+
+
+@pytest.fixture(autouse=True, params=[B.SPLC_MATMUL_FP32, B.SPLC_MATMUL_BF16X3], ids=["fp32", "bf16x3"])
+def matmul_mode(request):
+    B.sparseloco_set_matmul_mode(request.param)
+    assert B.sparseloco_get_matmul_mode() == request.param
+    yield request.param
+    B.sparseloco_set_matmul_mode(B.SPLC_MATMUL_FP32)
 
 
 def run_case(vocab, d, k, seed):
@@ -73,6 +86,10 @@ def test_coordinate_subspace_is_exact():
     assert np.array_equal(out_ts[:, keep], ts[:, keep]) and not out_ts[:, ~keep].any()
     assert np.array_equal(out_tp[:, ~keep], tp[:, ~keep] + ts[:, ~keep])
     assert np.array_equal(out_tp[:, keep], tp[:, keep])
+
+
+def test_matmul_mode_argument():
+    assert B.lib().sparseloco_set_matmul_mode(7) == B.SPLC_EINVAL
 
 
 def test_argument_checks():
