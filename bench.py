@@ -107,6 +107,20 @@ def cpu_baseline(rs, cfg, sample_tensors, quant=True, shapes=None):
 
 
 MFMA_FP32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+
+
+def mfma_roofline(kernel, flops, ms, math):
+    """Roofline entry of an MFMA-bound product.  With --math bf16x3 the matrix pipe executes six bf16 piece
+    products per fp32 product, and the bf16 peak is the one that applies."""
+    if math == "bf16x3":
+        ach = 6 * flops / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "kernel": kernel + ", bf16x3", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "fp32_equivalent_tflops": flops / (ms * 1e-3) / 1e12}
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": kernel, "achieved": ach, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": ach / MFMA_FP32_PEAK_TFLOPS, "traffic": None}
 
 
 def bench_reproject(args):
@@ -117,6 +131,7 @@ def bench_reproject(args):
     from oracle import subspace
     torch.cuda.set_device(0)
     vocab, d, k = args.vocab, args.d_model, args.k
+    B.sparseloco_set_matmul_mode(B.SPLC_MATMUL_BF16X3 if args.math == "bf16x3" else B.SPLC_MATMUL_FP32)
     g = torch.Generator(device="cuda").manual_seed(7)
     t_s = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
     t_perp = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
@@ -142,15 +157,14 @@ def bench_reproject(args):
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "embedding table %d x %d, subspace dimension k = %d (fp32, random orthonormal basis)"
-                               % (vocab, d, k), "algorithmic_flops": flops, "algorithmic_bytes": bytes_,
+                               % (vocab, d, k), "math": args.math, "algorithmic_flops": flops,
+                   "algorithmic_bytes": bytes_,
                    "hbm_gbs": bytes_ / (ms_ev * 1e-3) / 1e9},
         # a narrow basis (k <= 64: most of the paper's sweep) makes the five passes over the table the bound
-        "roofline": ({"bound": "hbm", "kernel": "project_narrow_kernel / gemm_f32_kernel (pass 1) + gemm_f32_kernel (pass 2)",
+        "roofline": ({"bound": "hbm", "kernel": "project_narrow_kernel / gemm_kernel (pass 1) + gemm_kernel (pass 2)",
                       "achieved": bytes_ / (ms_ev * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                       "frac": bytes_ / (ms_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None} if k <= 64 else
-                     {"bound": "mfma", "kernel": "gemm_f32_kernel (both passes)",
-                      "achieved": flops / (ms_ev * 1e-3) / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                      "frac": flops / (ms_ev * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, "traffic": None}),
+                     mfma_roofline("gemm_kernel (both passes)", flops, ms_ev, args.math)),
     }
     if not args.no_cpu:
         rows = min(vocab, 8192)
@@ -164,8 +178,9 @@ def bench_reproject(args):
         dt = (time.perf_counter() - t0) / reps
         result["cpu_baseline"] = {"value": rows / dt, "unit": "rows/s", "cores": os.cpu_count(), "kind": "oracle",
                                   "sample": "float64 numpy oracle on the first %d rows, %d repetitions" % (rows, reps)}
-    print("reproject %d x %d, k=%d: %.3f ms (events %.3f ms) = %.1f TFLOP/s fp32 = %.1f %% of the MFMA peak; %.0f GB/s"
-          % (vocab, d, k, ms, ms_ev, flops / (ms_ev * 1e-3) / 1e12,
+    print("reproject %d x %d, k=%d, %s products: %.3f ms (events %.3f ms) = %.1f TFLOP/s fp32-equivalent (%.1f %% of "
+          "the fp32 MFMA peak); %.0f GB/s"
+          % (vocab, d, k, args.math, ms, ms_ev, flops / (ms_ev * 1e-3) / 1e12,
              100 * flops / (ms_ev * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS, bytes_ / (ms_ev * 1e-3) / 1e9),
           file=sys.stderr, flush=True)
     print(json.dumps(result), flush=True)
@@ -179,6 +194,7 @@ def bench_project(args):
     from oracle import subspace
     torch.cuda.set_device(0)
     rows, seq, d, k, vocab = args.tokens, args.seq_len, args.d_model, args.k, args.vocab
+    B.sparseloco_set_matmul_mode(B.SPLC_MATMUL_BF16X3 if args.math == "bf16x3" else B.SPLC_MATMUL_FP32)
     g = torch.Generator(device="cuda").manual_seed(3)
     x = torch.randn(rows, d, generator=g, device="cuda")
     t_perp = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
@@ -218,12 +234,10 @@ def bench_project(args):
     narrow = k <= 64
     if narrow:
         gbs = 2 * bytes_dir / ((ms_p + ms_r) * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "project_narrow_kernel / gemm_f32_kernel (project) + gemm_f32_kernel (reconstruct)",
+        roofline = {"bound": "hbm", "kernel": "project_narrow_kernel / gemm_kernel (project) + gemm_kernel (reconstruct)",
                     "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None}
     else:
-        roofline = {"bound": "mfma", "kernel": "gemm_f32_kernel (project + reconstruct)", "achieved": ach,
-                    "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_FP32_PEAK_TFLOPS,
-                    "traffic": None}
+        roofline = mfma_roofline("gemm_kernel (project + reconstruct)", flops, ms_p + ms_r, args.math)
     result = {
         "metric": "stage-boundary tokens/sec (section 2.2: project to the subspace + reconstruct)",
         "value": rows / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -231,7 +245,7 @@ def bench_project(args):
         "data": "synthetic",
         "config": {"workload": "%d tokens (seq_len %d) x d %d, k = %d, T_perp %d x %d gathered by token, positional "
                                "table %d x %d" % (rows, seq, d, k, vocab, d, seq, d),
-                   "algorithmic_flops": flops, "algorithmic_bytes": 2 * bytes_dir,
+                   "math": args.math, "algorithmic_flops": flops, "algorithmic_bytes": 2 * bytes_dir,
                    "kernel_ms": {"project": ms_p, "reconstruct": ms_r}},
         "roofline": roofline,
     }
@@ -246,8 +260,9 @@ def bench_project(args):
         dt = (time.perf_counter() - t0) / reps
         result["cpu_baseline"] = {"value": n / dt, "unit": "tokens/s", "cores": os.cpu_count(), "kind": "oracle",
                                   "sample": "float64 numpy oracle on the first %d tokens, %d repetitions" % (n, reps)}
-    print("project %.3f ms + reconstruct %.3f ms for %d tokens (d %d, k %d): %.1f TFLOP/s fp32; %s roofline fraction %.2f"
-          % (ms_p, ms_r, rows, d, k, ach, roofline["bound"], roofline["frac"]), file=sys.stderr, flush=True)
+    print("project %.3f ms + reconstruct %.3f ms for %d tokens (d %d, k %d), %s products: %.1f TFLOP/s fp32-equivalent; "
+          "%s roofline fraction %.2f"
+          % (ms_p, ms_r, rows, d, k, args.math, ach, roofline["bound"], roofline["frac"]), file=sys.stderr, flush=True)
     print(json.dumps(result), flush=True)
 
 
@@ -261,6 +276,9 @@ def main():
     ap.add_argument("--vocab", type=int, default=32000)
     ap.add_argument("--d-model", type=int, default=2048)
     ap.add_argument("--k", type=int, default=256)
+    ap.add_argument("--math", choices=["fp32", "bf16x3"], default="fp32",
+                    help="--op reproject / project: how the dense products are formed (fp32 MFMA, or fp32 operands "
+                         "split into three bf16 pieces and six bf16 MFMAs per product)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None,
                     help="timed steps (default 20; 200 for the sub-millisecond --op reproject / project)")
