@@ -228,7 +228,8 @@ int sparseloco_get_matmul_mode(void);
  *   u: [d, k] row-major fp32, orthonormal columns (not checked), 1 <= k <= d.
  *   coeff_ws: device workspace of vocab * k floats owned by the caller; on return
  *   (after the stream reaches this point) it holds T_S U.
- * fp32 inputs, fp32 matrix-core arithmetic with fp32 accumulation; the result
+ * fp32 inputs, matrix-core products as set by sparseloco_set_matmul_mode (fp32
+ * by default), fp32 accumulation; the result
  * differs from exact arithmetic by the usual dot-product rounding of length d
  * and k.  Pointers 4-byte aligned; vocab < 2^31 - 128.
  */
@@ -245,7 +246,8 @@ int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, fl
  * (int32, clamped into [0, vocab)) and pos_embed [seq_len, d] are each optional
  * (NULL): with both NULL, project is the plain product used for the backward
  * pass, (grad x) U.  u: [d, k] row-major, 1 <= k <= d.  All arrays fp32 device
- * memory, 4-byte aligned; fp32 matrix-core arithmetic with fp32 accumulation.
+ * memory, 4-byte aligned; matrix-core products as set by sparseloco_set_matmul_mode
+ * (fp32 by default), fp32 accumulation.
  * The outputs are fully overwritten and must not overlap the inputs.
  */
 int sparseloco_subspace_project(const float* x, const float* t_perp, const int32_t* token_ids, int vocab,
