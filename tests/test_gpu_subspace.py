@@ -142,3 +142,47 @@ def test_project_and_reconstruct_match_the_oracle(rows, seq, d, k, vocab, use_pe
     want_h = subspace.reconstruct(out_t.cpu().numpy(), u, tp, tok, pos)
     got_h = out_h.cpu().numpy().astype(np.float64)
     assert np.all(np.linalg.norm(got_h - want_h, axis=1) <= tol), "reconstruct"
+
+
+def test_subspace_calls_replay_from_a_hip_graph():
+    """The matrix entry points only enqueue kernels, so they can be recorded into a HIP graph: three replays on
+    fresh inputs, with eager work and synchronisation in between, each equal to the eager result bit for bit."""
+    rows, seq, d, k, vocab = 500, 50, 256, 40, 64
+    gen = torch.Generator(device="cuda").manual_seed(17)
+    u = torch.from_numpy(subspace.orthonormal_basis(d, k, 3).astype(np.float32)).cuda()
+    x = torch.randn(rows, d, generator=gen, device="cuda")
+    tp = torch.randn(vocab, d, generator=gen, device="cuda") * 0.5
+    pos = torch.randn(seq, d, generator=gen, device="cuda") * 0.5
+    tok = torch.randint(0, vocab, (rows,), generator=gen, device="cuda", dtype=torch.int32)
+    ts = torch.randn(vocab, d, generator=gen, device="cuda")
+    xt, xh = torch.empty(rows, k, device="cuda"), torch.empty(rows, d, device="cuda")
+    ws = torch.empty(vocab * k, device="cuda")
+
+    def work(x_in, ts_io, tp_io, xt_out, xh_out):
+        B.sparseloco_subspace_project(x_in, u, xt_out, t_perp=tp_io, token_ids=tok, pos_embed=pos)
+        B.sparseloco_subspace_reconstruct(xt_out, u, xh_out, t_perp=tp_io, token_ids=tok, pos_embed=pos)
+        B.sparseloco_reproject_embedding(ts_io, tp_io, u, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    ts_g, tp_g = ts.clone(), tp.clone()
+    with torch.cuda.stream(side):
+        work(x, ts_g.clone(), tp_g.clone(), xt, xh)                 # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        work(x, ts_g, tp_g, xt, xh)
+    for rep in range(3):
+        x.copy_(torch.randn(rows, d, generator=gen, device="cuda"))
+        ts_g.copy_(torch.randn(vocab, d, generator=gen, device="cuda"))
+        tp_g.copy_(tp)
+        ts_e, tp_e = ts_g.clone(), tp_g.clone()
+        xt_e, xh_e = torch.empty_like(xt), torch.empty_like(xh)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        work(x, ts_e, tp_e, xt_e, xh_e)                              # eager, same inputs
+        torch.cuda.synchronize()
+        # the eager project / reconstruct ran before the eager re-projection changed tp_e, as in the graph
+        assert torch.equal(xt, xt_e) and torch.equal(xh, xh_e), "replay %d: stage boundary" % rep
+        assert torch.equal(ts_g, ts_e) and torch.equal(tp_g, tp_e), "replay %d: re-projection" % rep
