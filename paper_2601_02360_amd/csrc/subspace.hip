@@ -294,7 +294,15 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<MATH, TM_, TN_, Pro>())) 
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
-    const int m0 = blockIdx.y * TM_, n0 = blockIdx.x * TN_;
+    // Workgroups are handed to the eight XCDs round-robin by their linear number, and each XCD has an L2 of
+    // its own.  The column tiles of one row block all read the same rows of A, so they are given numbers that
+    // land on one XCD: XCD x takes the row blocks x, x + 8, ..., each with all of its column tiles in turn.
+    // (The grid is one-dimensional and padded to a multiple of eight row blocks; the surplus groups leave.)
+    const int col_tiles = (N + TN_ - 1) / TN_;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int row_block = (slot / col_tiles) * 8 + xcd;
+    const int m0 = row_block * TM_, n0 = (slot % col_tiles) * TN_;
+    if (m0 >= M) return;
 
     v16f acc[MI][NJ];
 #pragma unroll
@@ -740,7 +748,8 @@ int g_matmul_mode = SPLC_MATMUL_FP32;      // process-wide, set by sparseloco_se
 template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
 void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
                       hipStream_t st) {
-    dim3 grid((unsigned)((N + TN_ - 1) / TN_), (unsigned)((M + TM_ - 1) / TM_));
+    const int64_t row_blocks = ((int64_t)(M + TM_ - 1) / TM_ + 7) / 8 * 8;
+    dim3 grid((unsigned)(row_blocks * ((N + TN_ - 1) / TN_)));
     if (g_matmul_mode == SPLC_MATMUL_BF16X3)
         hipLaunchKernelGGL((gemm_kernel<MATH_BF16X3, TM_, TN_, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B,
                            ldb, M, N, K, pro, epi);
