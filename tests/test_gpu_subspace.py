@@ -186,3 +186,47 @@ def test_subspace_calls_replay_from_a_hip_graph():
         # the eager project / reconstruct ran before the eager re-projection changed tp_e, as in the graph
         assert torch.equal(xt, xt_e) and torch.equal(xh, xh_e), "replay %d: stage boundary" % rep
         assert torch.equal(ts_g, ts_e) and torch.equal(tp_g, tp_e), "replay %d: re-projection" % rep
+
+
+def test_random_shapes_of_all_three_calls():
+    """Eighty seeded random shapes around the tile sizes (rows, d and k on, just below and just above multiples of
+    16, 32, 64 and 128; either table present or absent), each call held to the bars of the tests above."""
+    rng = np.random.default_rng(12345)
+    for it in range(80):
+        rows = int(rng.choice([1, 7, 16, 17, 63, 64, 65, 129, 300, 1000, 2049]))
+        d = int(rng.choice([1, 4, 31, 32, 33, 64, 96, 100, 128, 160, 256, 257, 512, 1024]))
+        k = int(min(d, rng.choice([1, 2, 3, 4, 5, 8, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 100, 128, 129, 200, 256])))
+        seq, vocab = int(rng.integers(1, rows + 1)), int(rng.integers(1, 200))
+        use_perp, use_pos = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        what = "case %d: rows %d d %d k %d seq %d vocab %d perp %d pos %d" % (it, rows, d, k, seq, vocab, use_perp, use_pos)
+        u = subspace.orthonormal_basis(d, k, it).astype(np.float32)
+        x = rng.standard_normal((rows, d)).astype(np.float32)
+        tp = (rng.standard_normal((vocab, d)) * 0.5).astype(np.float32) if use_perp else None
+        tok = rng.integers(0, vocab, rows).astype(np.int32) if use_perp else None
+        pos = (rng.standard_normal((seq, d)) * 0.5).astype(np.float32) if use_pos else None
+        dev = lambda a: None if a is None else torch.from_numpy(a.copy()).cuda()
+        g_x, g_u, g_tp, g_tok, g_pos = dev(x), dev(u), dev(tp), dev(tok), dev(pos)
+        out_t = torch.full((rows, k), float("nan"), device="cuda")
+        B.sparseloco_subspace_project(g_x, g_u, out_t, t_perp=g_tp, token_ids=g_tok, pos_embed=g_pos)
+        # the roundings of fl(fl(x - t) - p) scale with the operands, not with t + p (which may cancel)
+        scale = np.linalg.norm(x.astype(np.float64), axis=1)
+        if tp is not None:
+            scale = scale + np.linalg.norm(tp[tok].astype(np.float64), axis=1)
+        if pos is not None:
+            scale = scale + np.linalg.norm(pos[np.arange(rows) % seq].astype(np.float64), axis=1)
+        tol = 8 * (np.sqrt(d) + np.sqrt(k)) * EPS * scale
+        got_t = out_t.cpu().numpy()
+        assert np.all(np.linalg.norm(got_t.astype(np.float64) - subspace.project(x, u, tp, tok, pos), axis=1) <= tol), what
+        out_h = torch.full((rows, d), float("nan"), device="cuda")
+        B.sparseloco_subspace_reconstruct(out_t, g_u, out_h, t_perp=g_tp, token_ids=g_tok, pos_embed=g_pos)
+        want_h = subspace.reconstruct(got_t, u, tp, tok, pos)
+        assert np.all(np.linalg.norm(out_h.cpu().numpy().astype(np.float64) - want_h, axis=1) <= tol), what
+        ts = (rng.standard_normal((vocab, d)) * 0.02).astype(np.float32)
+        tq = (rng.standard_normal((vocab, d)) * 0.02).astype(np.float32)
+        want_ts, want_tq = subspace.reproject(ts, tq, u)
+        g_ts, g_tq = dev(ts), dev(tq)
+        B.sparseloco_reproject_embedding(g_ts, g_tq, g_u, torch.empty(vocab * k, device="cuda"))
+        tol_r = 8 * (np.sqrt(d) + np.sqrt(k)) * EPS * np.linalg.norm(ts.astype(np.float64), axis=1)
+        assert np.all(np.linalg.norm(g_ts.cpu().numpy().astype(np.float64) - want_ts, axis=1) <= tol_r), what
+        assert np.all(np.linalg.norm(g_tq.cpu().numpy().astype(np.float64) - want_tq, axis=1) <=
+                      tol_r + 2 * EPS * np.linalg.norm(tq.astype(np.float64), axis=1)), what
