@@ -209,7 +209,7 @@ int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas,
  *                       step.  Operands must be finite and normal-or-zero.
  * A projection onto at most 32 columns (16 with both tables of section 2.2) is
  * bound by memory traffic and always uses fp32 products.
- * Measured: 1.2-1.45 times the fp32 rate (the chip lowers its clock under the
+ * Measured: 1.15-1.45 times the fp32 rate (the chip lowers its clock under the
  * bf16 matrix load, which caps the gain).
  * sparseloco_set_matmul_mode returns SPLC_EINVAL for another value.
  */

@@ -764,16 +764,25 @@ void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, 
 //   a product with the basis as the N x K operand has K = k: up to K = 192 the K loop is so short that
 //            64 x 64 tiles win (more, smaller workgroups per compute unit overlap one group's epilogue
 //            with another's products); beyond that the reconstruction (light_epilogue: one store per
-//            output) still prefers 64 rows.
+//            output) still prefers 64 rows;
+//   with split-bf16 products (measured separately): see below.
 template <bool B_NK, class Pro, class Epi>
 void launch_gemm(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
                  hipStream_t st, bool light_epilogue = false) {
     auto groups = [&](int tm, int tn) { return (int64_t)((M + tm - 1) / tm) * ((N + tn - 1) / tn); };
     bool wide = ((N + 63) / 64) % 2 == 0;
     bool tall;
-    if (B_NK && K <= 192) wide = tall = false;
-    else if (light_epilogue) tall = false;
-    else tall = groups(128, wide ? 128 : 64) >= 2 * 256;
+    if (g_matmul_mode == SPLC_MATMUL_BF16X3) {
+        // split operands: a tile's matrix work is a third as long and splitting costs per staged value, so the
+        // large tile, which stages fewest values per product, wins wherever it leaves 1.5 groups per compute unit
+        tall = B_NK || groups(128, wide ? 128 : 64) >= 3 * 128;
+    } else if (B_NK && K <= 192) {
+        wide = tall = false;
+    } else if (light_epilogue) {
+        tall = false;
+    } else {
+        tall = groups(128, wide ? 128 : 64) >= 2 * 256;
+    }
     if (tall && wide) launch_gemm_tile<128, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
     else if (tall) launch_gemm_tile<128, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
     else if (wide) launch_gemm_tile<64, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
