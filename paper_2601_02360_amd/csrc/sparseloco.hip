@@ -1109,6 +1109,24 @@ int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const 
         plan->n_gen_f32 += cd.vec == 0;
         plan->n_gen_bf16 += cd.vec != 3;
     }
+    if (tiled) {
+        // Workgroups go to the eight XCDs round-robin by number.  Neighbouring tiles of a tile row continue each
+        // other's 256-byte row segments (and share the cache lines on their common edge when the row length is
+        // no multiple of 32 floats), so each XCD is given a run of consecutive tiles (inside each class of the
+        // table) instead of every eighth one.  Only the order of processing changes: a chunk's number, and with
+        // it the place of its pairs in the message, is its `id`.
+        size_t start = 0;
+        while (start < table.size()) {
+            size_t end = start;
+            auto cls = [](const ChunkDesc& d) { return d.vec == 0 ? 0 : (d.vec == 1 ? 1 : 2); };
+            while (end < table.size() && cls(table[end]) == cls(table[start])) ++end;
+            const std::vector<ChunkDesc> seg(table.begin() + (ptrdiff_t)start, table.begin() + (ptrdiff_t)end);
+            size_t next = 0;
+            for (size_t r = 0; r < 8; ++r)
+                for (size_t pos = start + (r + 8 - start % 8) % 8; pos < end; pos += 8) table[pos] = seg[next++];
+            start = end;
+        }
+    }
     int rc = SPLC_OK;
     // largest pointer table of any call: aggregate (2 per replica + 2 per tensor), compress (3 per
     // tensor), compress_batch ((1 + 2 R) per tensor + 2 R), aggregate_update with resets
