@@ -53,3 +53,17 @@ def test_null_plan_is_rejected():
     assert L.sparseloco_outer_update(None, None, None, 1.0, None) == B.SPLC_EINVAL
     assert L.sparseloco_plan_set_select(None, 0) == B.SPLC_EINVAL
     L.sparseloco_plan_destroy(None)
+
+
+def test_matmul_mode_switch_needs_no_gpu():
+    """The process-wide matmul mode: fp32 by default, accepted values stick, anything else is refused."""
+    L = B.lib()
+    assert L.sparseloco_get_matmul_mode() == B.SPLC_MATMUL_FP32
+    try:
+        assert L.sparseloco_set_matmul_mode(B.SPLC_MATMUL_BF16X3) == B.SPLC_OK
+        assert L.sparseloco_get_matmul_mode() == B.SPLC_MATMUL_BF16X3
+        assert L.sparseloco_set_matmul_mode(2) == B.SPLC_EINVAL
+        assert L.sparseloco_set_matmul_mode(-1) == B.SPLC_EINVAL
+        assert L.sparseloco_get_matmul_mode() == B.SPLC_MATMUL_BF16X3
+    finally:
+        assert L.sparseloco_set_matmul_mode(B.SPLC_MATMUL_FP32) == B.SPLC_OK
