@@ -67,7 +67,8 @@ enum {
     SPLC_EALIGN = -2,            /* a tensor pointer is not 4-byte aligned */
     SPLC_ENOMEM = -3,            /* host or device allocation failed */
     SPLC_EHIP = -4,              /* a HIP runtime call failed */
-    SPLC_EPLAN = -5              /* call does not match the plan (quantiser mode, device) */
+    SPLC_EPLAN = -5,             /* call does not match the plan (quantiser mode, device) */
+    SPLC_ETOOBIG = -6            /* problem larger than the fixed workspace of a call that allocates nothing */
 };
 
 enum { SPLC_F32 = 0, SPLC_BF16 = 1 };
@@ -235,6 +236,22 @@ int sparseloco_get_matmul_mode(void);
  */
 int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, float* coeff_ws,
                                    int64_t vocab, int d, int k, void* stream);
+
+/*
+ * sparseloco_reproject_embedding for callers that cannot allocate device memory or hold a workspace of their
+ * own: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same kernels, same
+ * results, bit for bit; the coefficients T_S U go to a fixed array of SPLC_NOALLOC_MAX_COEFF floats (32 MiB)
+ * that is part of the library's code object: every GPU the library runs on holds one copy from load time until
+ * the process ends.  The call makes no hipMalloc / hipFree and no other allocating call; its first call on a
+ * device looks the array's address up once (do that first call outside a graph capture).
+ *   vocab * k <= SPLC_NOALLOC_MAX_COEFF, else SPLC_ETOOBIG (nothing is enqueued).
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams
+ * without an ordering between them) race on it.  Nothing in it has to be cleared between calls -- pass 1 writes
+ * every coefficient pass 2 reads -- and its contents after the call are unspecified.
+ */
+#define SPLC_NOALLOC_MAX_COEFF (8 * 1024 * 1024)
+int sparseloco_reproject_embedding_noalloc(float* t_s, float* t_perp, const float* u,
+                                           int64_t vocab, int d, int k, void* stream);
 
 /*
  * Section 2.2 ("Communication-Efficient Pipeline Parallelism"): what a pipeline

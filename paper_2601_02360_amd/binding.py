@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsparseloco.so")
 
 SPLC_CHUNK = 4096
-SPLC_OK, SPLC_EINVAL, SPLC_EALIGN, SPLC_ENOMEM, SPLC_EHIP, SPLC_EPLAN = 0, -1, -2, -3, -4, -5
+SPLC_OK, SPLC_EINVAL, SPLC_EALIGN, SPLC_ENOMEM, SPLC_EHIP, SPLC_EPLAN, SPLC_ETOOBIG = 0, -1, -2, -3, -4, -5, -6
+SPLC_NOALLOC_MAX_COEFF = 8 * 1024 * 1024
 SPLC_F32, SPLC_BF16 = 0, 1
 SPLC_DELTA_FROM_PARAMS, SPLC_DELTA_DIRECT = 0, 1
 SPLC_QUANT_NONE, SPLC_QUANT_2BIT = 0, 1
@@ -31,7 +32,7 @@ EXPORTS = [
     "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
     "sparseloco_plan_set_select", "sparseloco_compress", "sparseloco_aggregate",
     "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
-    "sparseloco_reproject_embedding", "sparseloco_subspace_project", "sparseloco_subspace_reconstruct",
+    "sparseloco_reproject_embedding", "sparseloco_reproject_embedding_noalloc", "sparseloco_subspace_project", "sparseloco_subspace_reconstruct",
     "sparseloco_set_matmul_mode", "sparseloco_get_matmul_mode", "sparseloco_strerror",
 ]
 
@@ -87,6 +88,8 @@ def lib():
         L.sparseloco_compress_batch.argtypes = [vp, i32, pp, ctypes.POINTER(pp), ctypes.POINTER(pp), f32, pp, pp, vp]
         L.sparseloco_reproject_embedding.restype = i32
         L.sparseloco_reproject_embedding.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp]
+        L.sparseloco_reproject_embedding_noalloc.restype = i32
+        L.sparseloco_reproject_embedding_noalloc.argtypes = [vp, vp, vp, i64, i32, i32, vp]
         for fn in (L.sparseloco_subspace_project, L.sparseloco_subspace_reconstruct):
             fn.restype = i32
             fn.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, i64, i32, i32, vp]
@@ -273,6 +276,20 @@ def sparseloco_reproject_embedding(t_s: torch.Tensor, t_perp: torch.Tensor, u: t
                                               int(vocab), int(d), int(k), _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_reproject_embedding")
+
+
+def sparseloco_reproject_embedding_noalloc(t_s: torch.Tensor, t_perp: torch.Tensor, u: torch.Tensor, *,
+                                           stream=None) -> None:
+    """sparseloco_reproject_embedding with the coefficients in the library's fixed per-GPU array (no allocation,
+    no caller workspace); vocab * k <= SPLC_NOALLOC_MAX_COEFF."""
+    vocab, d = t_s.shape
+    k = u.shape[1]
+    assert t_perp.shape == t_s.shape and u.shape[0] == d
+    assert all(x.dtype == torch.float32 and x.is_contiguous() for x in (t_s, t_perp, u))
+    rc = lib().sparseloco_reproject_embedding_noalloc(t_s.data_ptr(), t_perp.data_ptr(), u.data_ptr(), int(vocab),
+                                                      int(d), int(k), _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_reproject_embedding_noalloc")
 
 
 def sparseloco_set_matmul_mode(mode: int) -> None:

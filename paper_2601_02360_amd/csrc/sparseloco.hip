@@ -1373,6 +1373,7 @@ const char* sparseloco_strerror(int status) {
         case SPLC_ENOMEM: return "allocation failed";
         case SPLC_EHIP: return "HIP runtime call failed";
         case SPLC_EPLAN: return "call does not match the plan";
+        case SPLC_ETOOBIG: return "problem exceeds the fixed workspace of this call";
         default: return "unknown status";
     }
 }

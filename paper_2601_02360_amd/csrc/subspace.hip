@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "sparseloco.h"
@@ -801,13 +802,11 @@ extern "C" int sparseloco_set_matmul_mode(int mode) {
 
 extern "C" int sparseloco_get_matmul_mode(void) { return g_matmul_mode; }
 
-extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, float* coeff_ws,
-                                              int64_t vocab, int d, int k, void* stream) {
-    if (!t_s || !t_perp || !u || !coeff_ws) return SPLC_EINVAL;
-    if (vocab < 0 || vocab > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d) return SPLC_EINVAL;
-    if (!aligned4(t_s) || !aligned4(t_perp) || !aligned4(u) || !aligned4(coeff_ws)) return SPLC_EALIGN;
-    if (vocab == 0) return SPLC_OK;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+namespace {
+
+// Both passes of the re-projection with the coefficients in `coeff_ws` (vocab * k floats of device memory).
+int reproject_impl(float* t_s, float* t_perp, const float* u, float* coeff_ws, int64_t vocab, int d, int k,
+                   hipStream_t st) {
     const int M = (int)vocab;
     // pass 1: coeff = T_S U            (M x k) = (M x d)(d x k)
     if (narrow_applies(d, k, HighRank{nullptr, nullptr, 0, nullptr, 1, (int64_t)d}))
@@ -818,6 +817,61 @@ extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const f
     launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, UpdateEmbedding{t_s, t_perp, (int64_t)d},
                       st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
+}
+
+int check_reproject_args(const float* t_s, const float* t_perp, const float* u, int64_t vocab, int d, int k) {
+    if (!t_s || !t_perp || !u) return SPLC_EINVAL;
+    if (vocab < 0 || vocab > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d) return SPLC_EINVAL;
+    if (!aligned4(t_s) || !aligned4(t_perp) || !aligned4(u)) return SPLC_EALIGN;
+    return SPLC_OK;
+}
+
+// Coefficient workspace of sparseloco_reproject_embedding_noalloc: one array per GPU, part of the code object, so
+// it exists from the moment the library is loaded on a device until the process ends.  Host code never uses the
+// name below as an address; it asks the runtime for the array's device address once per device (scratch_of) and
+// passes that pointer to the kernels.
+static __device__ __align__(256) float scratch[SPLC_NOALLOC_MAX_COEFF];
+
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};          // per device: address of that device's copy of `scratch`
+std::mutex g_scratch_mutex;
+
+int scratch_of(float** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SPLC_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return SPLC_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SPLC_EHIP;
+        g_scratch_ptr[dev] = static_cast<float*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SPLC_OK;
+}
+
+}  // namespace
+
+extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, float* coeff_ws,
+                                              int64_t vocab, int d, int k, void* stream) {
+    if (!coeff_ws) return SPLC_EINVAL;
+    int rc = check_reproject_args(t_s, t_perp, u, vocab, d, k);
+    if (rc != SPLC_OK) return rc;
+    if (!aligned4(coeff_ws)) return SPLC_EALIGN;
+    if (vocab == 0) return SPLC_OK;
+    return reproject_impl(t_s, t_perp, u, coeff_ws, vocab, d, k, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int sparseloco_reproject_embedding_noalloc(float* t_s, float* t_perp, const float* u, int64_t vocab, int d,
+                                                      int k, void* stream) {
+    int rc = check_reproject_args(t_s, t_perp, u, vocab, d, k);
+    if (rc != SPLC_OK) return rc;
+    if (vocab * (int64_t)k > (int64_t)SPLC_NOALLOC_MAX_COEFF) return SPLC_ETOOBIG;
+    if (vocab == 0) return SPLC_OK;
+    float* ws = nullptr;
+    if ((rc = scratch_of(&ws)) != SPLC_OK) return rc;
+    // Nothing has to start at zero: pass 1 writes every coefficient that pass 2 reads.
+    return reproject_impl(t_s, t_perp, u, ws, vocab, d, k, static_cast<hipStream_t>(stream));
 }
 
 namespace {
