@@ -10,6 +10,8 @@ timed on a bounded sample of the same workload on the host cores.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-cpu]
 
+Other legs: --op reproject / project (the dense products of sections 2.4 / 2.2 against the MFMA or HBM
+roofline) and --op stream (what the chip streams for the kernels' access patterns: the practical ceiling).
 Prints ONE JSON line on stdout; a per-kernel breakdown goes to stderr.
 """
 from __future__ import annotations
@@ -36,14 +38,17 @@ def algorithmic_bytes(n_params, n_chunks, kappa, R, direct_bf16, quant=True):
     return compress, aggregate, update
 
 
-def read_traffic(workload_name):
-    """HBM bytes per compress launch measured with rocprofv3 --pmc (profiles/), or None."""
-    path = os.path.join(ROOT, "profiles", "compress_%s_hbm_traffic.txt" % workload_name)
+def read_traffic(workload_name, layout="flat"):
+    """HBM bytes per compress launch as measured earlier with rocprofv3 --pmc and stored under profiles/
+    (a counter run cannot share a process with the timed run), and the file it came from; (None, None) if
+    this workload has no stored measurement."""
+    name = "compress_%s%s_hbm_traffic.txt" % (workload_name, "" if layout == "flat" else "_" + layout)
+    path = os.path.join(ROOT, "profiles", name)
     try:
         m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
+        return (float(m.group(1)), "stored: profiles/" + name) if m else (None, None)
     except OSError:
-        return None
+        return None, None
 
 
 def cpu_baseline(rs, cfg, sample_tensors, quant=True, shapes=None):
@@ -128,23 +133,23 @@ def bench_reproject(args):
     import numpy as np
     import torch
     from paper_2601_02360_amd import binding as B
-    from oracle import subspace
+    from paper_2601_02360_amd import workloads as W
     torch.cuda.set_device(0)
     vocab, d, k = args.vocab, args.d_model, args.k
-    B.sparseloco_set_matmul_mode(B.SPLC_MATMUL_BF16X3 if args.math == "bf16x3" else B.SPLC_MATMUL_FP32)
+    mm = B.SPLC_MATMUL_BF16X3 if args.math == "bf16x3" else B.SPLC_MATMUL_FP32
     g = torch.Generator(device="cuda").manual_seed(7)
     t_s = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
     t_perp = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
-    u = torch.from_numpy(subspace.orthonormal_basis(d, k, seed=11).astype(np.float32)).cuda()   # input generation only
+    u = W.orthonormal_basis(d, k, 11, "cuda")
     ws = torch.empty(vocab * k, device="cuda")
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for _ in range(args.warmup):
-        B.sparseloco_reproject_embedding(t_s, t_perp, u, ws)
+        B.sparseloco_reproject_embedding(t_s, t_perp, u, ws, matmul=mm)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i][0].record()
-        B.sparseloco_reproject_embedding(t_s, t_perp, u, ws)
+        B.sparseloco_reproject_embedding(t_s, t_perp, u, ws, matmul=mm)
         ev[i][1].record()
     torch.cuda.synchronize()
     ms = 1e3 * (time.perf_counter() - t0) / args.steps
@@ -167,6 +172,7 @@ def bench_reproject(args):
                      mfma_roofline("gemm_kernel (both passes)", flops, ms_ev, args.math)),
     }
     if not args.no_cpu:
+        from oracle import subspace
         rows = min(vocab, 8192)
         a, b = t_s[:rows].cpu().numpy(), t_perp[:rows].cpu().numpy()
         un = u.cpu().numpy()
@@ -191,16 +197,16 @@ def bench_project(args):
     import numpy as np
     import torch
     from paper_2601_02360_amd import binding as B
-    from oracle import subspace
+    from paper_2601_02360_amd import workloads as W
     torch.cuda.set_device(0)
     rows, seq, d, k, vocab = args.tokens, args.seq_len, args.d_model, args.k, args.vocab
-    B.sparseloco_set_matmul_mode(B.SPLC_MATMUL_BF16X3 if args.math == "bf16x3" else B.SPLC_MATMUL_FP32)
+    mm = B.SPLC_MATMUL_BF16X3 if args.math == "bf16x3" else B.SPLC_MATMUL_FP32
     g = torch.Generator(device="cuda").manual_seed(3)
     x = torch.randn(rows, d, generator=g, device="cuda")
     t_perp = torch.randn(vocab, d, generator=g, device="cuda") * 0.02
     pos = torch.randn(seq, d, generator=g, device="cuda") * 0.02
     tok = torch.randint(0, vocab, (rows,), generator=g, device="cuda", dtype=torch.int32)
-    u = torch.from_numpy(subspace.orthonormal_basis(d, k, seed=11).astype(np.float32)).cuda()   # input generation only
+    u = W.orthonormal_basis(d, k, 11, "cuda")
     xt = torch.empty(rows, k, device="cuda")
     xh = torch.empty(rows, d, device="cuda")
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -208,10 +214,10 @@ def bench_project(args):
     def step(i=None):
         if i is not None:
             ev[i][0].record()
-        B.sparseloco_subspace_project(x, u, xt, t_perp=t_perp, token_ids=tok, pos_embed=pos)
+        B.sparseloco_subspace_project(x, u, xt, t_perp=t_perp, token_ids=tok, pos_embed=pos, matmul=mm)
         if i is not None:
             ev[i][1].record()
-        B.sparseloco_subspace_reconstruct(xt, u, xh, t_perp=t_perp, token_ids=tok, pos_embed=pos)
+        B.sparseloco_subspace_reconstruct(xt, u, xh, t_perp=t_perp, token_ids=tok, pos_embed=pos, matmul=mm)
         if i is not None:
             ev[i][2].record()
 
@@ -250,6 +256,7 @@ def bench_project(args):
         "roofline": roofline,
     }
     if not args.no_cpu:
+        from oracle import subspace
         n = min(rows, 4096)
         a, tp, ps, tk, un = (t.cpu().numpy() for t in (x[:n], t_perp, pos, tok[:n], u))
         t0 = time.perf_counter()
@@ -266,11 +273,61 @@ def bench_project(args):
     print(json.dumps(result), flush=True)
 
 
+def bench_stream(args):
+    """What the chip streams for the access patterns of the outer-step kernels (one 256-lane workgroup per 4096
+    floats, 16-byte non-temporal accesses): the practical ceiling of the HBM roofline."""
+    import torch
+    from paper_2601_02360_amd import binding as B
+    torch.cuda.set_device(0)
+    n = (args.stream_elems // 4096) * 4096
+    a, b, c = (torch.empty(n, device="cuda").normal_() for _ in range(3))
+    sink = torch.zeros(1, device="cuda")
+    patterns = [("read", B.SPLC_STREAM_READ, 4), ("write", B.SPLC_STREAM_WRITE, 4), ("copy_1r1w", B.SPLC_STREAM_COPY, 8),
+                ("update_2r1w", B.SPLC_STREAM_R2W1, 12), ("compress_3r1w", B.SPLC_STREAM_R3W1, 16)]
+    out = {}
+    t_all = time.perf_counter()
+    for name, pat, bpe in patterns:
+        for _ in range(args.warmup):
+            B.sparseloco_stream_probe(pat, a, b, c, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.sparseloco_stream_probe(pat, a, b, c, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out[name] = {"ms": ms, "gbs": bpe * n / (ms * 1e-3) / 1e9}
+        print("stream %-14s %8.3f ms  %7.0f GB/s" % (name, ms, out[name]["gbs"]), file=sys.stderr, flush=True)
+    # the library's elementwise kernel with the compress kernel's pattern, as an independent reference
+    d = torch.empty_like(a)
+    for _ in range(3):
+        torch.addcmul(a, b, c, value=0.5, out=d)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        torch.addcmul(a, b, c, value=0.5, out=d)
+    e1.record()
+    torch.cuda.synchronize()
+    out["torch_addcmul_3r1w"] = {"ms": e0.elapsed_time(e1) / args.steps,
+                                 "gbs": 16.0 * n / (e0.elapsed_time(e1) / args.steps * 1e-3) / 1e9}
+    best = out["compress_3r1w"]
+    result = {"metric": "streamed bytes/sec for the compress kernel's access pattern (3 reads + 1 in-place write)",
+              "value": best["gbs"] * 1e9, "unit": "B/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+              "ms_per_step": best["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+              "dtype": "f32", "data": "synthetic",
+              "config": {"workload": "stream probes over %d-float arrays (%.2f GB each)" % (n, 4 * n / 1e9),
+                         "patterns": out, "wall_s": time.perf_counter() - t_all},
+              "roofline": {"bound": "hbm", "kernel": "stream_kernel<3 reads + 1 write>", "achieved": best["gbs"],
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["gbs"] / HBM_PEAK_GBS, "traffic": None}}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", choices=["outer_step", "reproject", "project"], default="outer_step",
+    ap.add_argument("--op", choices=["outer_step", "reproject", "project", "stream"], default="outer_step",
                     help="outer_step (default, the headline); reproject: section 2.4's embedding re-projection; "
-                         "project: section 2.2's stage boundary (project + reconstruct)")
+                         "project: section 2.2's stage boundary (project + reconstruct); stream: what the chip "
+                         "streams for the kernels' access patterns")
     ap.add_argument("--tokens", type=int, default=16384)
     ap.add_argument("--seq-len", type=int, default=1024)
     ap.add_argument("--vocab", type=int, default=32000)
@@ -279,6 +336,7 @@ def main():
     ap.add_argument("--math", choices=["fp32", "bf16x3"], default="fp32",
                     help="--op reproject / project: how the dense products are formed (fp32 MFMA, or fp32 operands "
                          "split into three bf16 pieces and six bf16 MFMAs per product)")
+    ap.add_argument("--stream-elems", type=int, default=887_685_120, help="--op stream: floats per array")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None,
                     help="timed steps (default 20; 200 for the sub-millisecond --op reproject / project)")
@@ -293,10 +351,13 @@ def main():
     ap.add_argument("--layout", choices=["flat", "tile"], default="flat",
                     help="flat: chunks of 4096 consecutive elements (default); tile: 64 x 64 tiles of each matrix")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="time the three-call outer step only (no fused / batched / graph variants, no references): "
+                         "for profiler runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
-    short_op = args.op != "outer_step"
+    short_op = args.op in ("reproject", "project")
     if args.steps is None:
         args.steps = 200 if short_op else 20
     if args.warmup is None:
@@ -319,6 +380,9 @@ def main():
     if args.op == "project":
         bench_project(args)
         return
+    if args.op == "stream":
+        bench_stream(args)
+        return
     torch.cuda.set_device(0)
     cfg = dict(W.WORKLOADS[args.workload])
     if args.kappa:
@@ -337,81 +401,62 @@ def main():
     plan = B.Plan(shapes if tiled else rs.numels, cfg["kappa"], quant, tiled=tiled)
     msgs = [plan.message_buffers() for _ in range(R)]
     dbar = [torch.empty(n, device="cuda") for n in rs.numels]
-    t_theta = B.ptr_table(rs.theta_outer)
-    t_dbar = B.ptr_table(dbar)
-    t_ef = [B.ptr_table(rs.ef[r]) for r in range(R)]
-    t_src = [B.ptr_table(rs.delta[r] if rs.direct else rs.theta_local[r]) for r in range(R)]
-    t_pairs = B.ptr_table([m[0] for m in msgs])
-    t_aux = B.ptr_table([m[1] for m in msgs])
+    # every tensor list is bound once; the timed calls only enqueue kernels
+    b_theta, b_dbar = plan.bind(rs.theta_outer), plan.bind(dbar)
+    b_ef = plan.bind(rs.ef)
+    b_src = plan.bind(rs.delta, torch.bfloat16) if rs.direct else plan.bind(rs.theta_local)
+    b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
     stream = torch.cuda.current_stream()
+    beta, lr = cfg["beta"], cfg["outer_lr"]
 
     ev_c = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(R)]
             for _ in range(args.steps)]
     ev_a = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             for _ in range(args.steps)]
 
+    def compress(r):
+        if rs.direct:
+            B.sparseloco_compress(plan, b_ef, msgs[r][0], msgs[r][1], beta, delta=b_src, replica=r, stream=stream)
+        else:
+            B.sparseloco_compress(plan, b_ef, msgs[r][0], msgs[r][1], beta, theta_outer=b_theta, theta_local=b_src,
+                                  replica=r, stream=stream)
+
     def step(k=None):
         for r in range(R):
             if k is not None:
                 ev_c[k][r][0].record(stream)
-            if rs.direct:
-                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], delta=t_src[r],
-                                      delta_dtype=B.SPLC_BF16, stream=stream)
-            else:
-                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], theta_outer=t_theta,
-                                      theta_local=t_src[r], stream=stream)
+            compress(r)
             if k is not None:
                 ev_c[k][r][1].record(stream)
         if k is not None:
             ev_a[k][0].record(stream)
-        B.sparseloco_aggregate(plan, t_pairs, t_aux, t_dbar, stream=stream)
+        B.sparseloco_aggregate(plan, b_msgs, b_dbar, stream=stream)
         if k is not None:
             ev_a[k][1].record(stream)
-        B.sparseloco_outer_update(plan, t_theta, t_dbar, cfg["outer_lr"], stream=stream)
+        B.sparseloco_outer_update(plan, b_theta, b_dbar, lr, stream=stream)
         if k is not None:
             ev_a[k][2].record(stream)
 
     def fused_step():
         for r in range(R):
-            if rs.direct:
-                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], delta=t_src[r],
-                                      delta_dtype=B.SPLC_BF16, stream=stream)
-            else:
-                B.sparseloco_compress(plan, t_ef[r], msgs[r][0], msgs[r][1], cfg["beta"], theta_outer=t_theta,
-                                      theta_local=t_src[r], stream=stream)
-        B.sparseloco_aggregate_update(plan, t_pairs, t_aux, t_theta, cfg["outer_lr"], stream=stream)
+            compress(r)
+        B.sparseloco_aggregate_update(plan, b_msgs, b_theta, lr, stream=stream)
 
-    # the same outer step with line 5 in one pass (sparseloco_aggregate_update, no dense mean written):
-    # reported beside the headline, which stays at the three-call boundary
-    for _ in range(args.warmup):
-        fused_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        fused_step()
-    torch.cuda.synchronize()
-    ms_fused = 1e3 * (time.perf_counter() - t0) / args.steps
+    def batched_step():
+        B.sparseloco_compress_batch(plan, b_theta, b_src, b_ef, b_msgs, beta, stream=stream)
+        B.sparseloco_aggregate_update(plan, b_msgs, b_theta, lr, stream=stream)
 
-    # single-node simulation path: all R replicas in one compress launch (theta_outer read once per
-    # chunk), line 5 fused.  Same inputs, same outputs; fewer bytes actually moved.
-    ms_batched = None
-    if not rs.direct and R <= 64:
-        t2_tl = B.ptr_table_2d(t_src)
-        t2_ef = B.ptr_table_2d(t_ef)
-
-        def batched_step():
-            B.sparseloco_compress_batch(plan, t_theta, t2_tl, t2_ef, t_pairs, t_aux, cfg["beta"], stream=stream)
-            B.sparseloco_aggregate_update(plan, t_pairs, t_aux, t_theta, cfg["outer_lr"], stream=stream)
-
+    def timed(fn):
         for _ in range(args.warmup):
-            batched_step()
+            fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            batched_step()
+            fn()
         torch.cuda.synchronize()
-        ms_batched = 1e3 * (time.perf_counter() - t0) / args.steps
+        return 1e3 * (time.perf_counter() - t0) / args.steps
 
+    # ---- the headline: the three-call outer step, timed first, W + K steps away from the seeded inputs
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -421,28 +466,69 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # Which selection path the timed launches took: one more outer step (same state distribution, outside the
+    # timed region) with the library's diagnostic counter switched on.
+    counter = torch.zeros(1, dtype=torch.int32, device="cuda")
+    plan.set_radix_counter(counter)
+    for r in range(R):
+        compress(r)
+    torch.cuda.synchronize()
+    plan.set_radix_counter(None)
+    radix_selections = int(counter.item())
+
+    ms_fused = ms_batched = ms_graph = None
+    stream_ref_gbs = probe_gbs = None
+    if not args.only_headline:
+        # the same outer step with line 5 in one pass (sparseloco_aggregate_update, no dense mean written):
+        # reported beside the headline, which stays at the three-call boundary
+        ms_fused = timed(fused_step)
+        # single-node simulation path: all R replicas in one compress launch (theta_outer read once per
+        # chunk), line 5 fused.  Same inputs, same outputs; fewer bytes actually moved.
+        if not rs.direct:
+            ms_batched = timed(batched_step)
+        # the three-call step recorded once into a HIP graph and replayed (the calls only enqueue kernels):
+        # what a launch-bound small parameter set gains
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        saved, stream = stream, side
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        stream = saved
+        torch.cuda.synchronize()
+        ms_graph = timed(graph.replay)
+
     if args.copy_calibration:
         src = torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_()
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
 
-    # Reference point for the roofline fraction (outside the timed region): what a plain library kernel with
-    # the compress kernel's access pattern -- three streamed reads, one streamed write -- reaches on this machine.
-    ref = [torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_() for _ in range(4)]
-    for _ in range(3):
-        torch.addcmul(ref[0], ref[1], ref[2], value=0.5, out=ref[3])
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(10):
-        torch.addcmul(ref[0], ref[1], ref[2], value=0.5, out=ref[3])
-    e1.record()
-    torch.cuda.synchronize()
-    stream_ref_gbs = 10 * 16.0 * (1 << 28) / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del ref
-    print("reference: torch.addcmul over 1 GiB arrays (3 reads + 1 write) streams %.0f GB/s on this box"
-          % stream_ref_gbs, file=sys.stderr, flush=True)
+    if not args.only_headline:
+        # Reference points for the roofline fraction (outside the timed region): what a plain library kernel with
+        # the compress kernel's access pattern -- three streamed reads, one streamed write -- reaches on this
+        # box, and what this library's own probe with the kernels' launch shape reaches.
+        ref = [torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_() for _ in range(4)]
+        sink = torch.zeros(1, device="cuda")
+
+        def gbs_of(fn, reps=10):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return reps * 16.0 * (1 << 28) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        stream_ref_gbs = gbs_of(lambda: torch.addcmul(ref[0], ref[1], ref[2], value=0.5, out=ref[3]))
+        probe_gbs = gbs_of(lambda: B.sparseloco_stream_probe(B.SPLC_STREAM_R3W1, ref[0], ref[1], ref[2], sink))
+        del ref
+        print("reference: 3 reads + 1 write over 1 GiB arrays stream %.0f GB/s (torch.addcmul) / %.0f GB/s (the "
+              "library's probe with the kernels' launch shape) on this box" % (stream_ref_gbs, probe_gbs),
+              file=sys.stderr, flush=True)
 
     ms_step = 1e3 * elapsed / args.steps
     n = rs.num_params
@@ -455,16 +541,23 @@ def main():
     gbs = lambda b, ms: b / (ms * 1e-3) / 1e9
     ach = gbs(b_c, avg(ms_c))
     total_bytes = R * b_c + b_a + b_u
-    print("per launch: compress %.3f ms (%.0f GB/s algorithmic), aggregate %.3f ms (%.0f GB/s), update %.3f ms "
-          "(%.0f GB/s); whole step %.3f ms = %.0f GB/s algorithmic = %.1f %% of HBM peak"
+    print("per launch: compress %.4f ms (%.0f GB/s algorithmic), aggregate %.4f ms (%.0f GB/s), update %.4f ms "
+          "(%.0f GB/s); whole step %.4f ms = %.0f GB/s algorithmic = %.1f %% of HBM peak"
           % (avg(ms_c), ach, avg(ms_a), gbs(b_a, avg(ms_a)), avg(ms_u), gbs(b_u, avg(ms_u)), ms_step,
              gbs(total_bytes, ms_step), 100 * gbs(total_bytes, ms_step) / HBM_PEAK_GBS), file=sys.stderr, flush=True)
-    print("with aggregate+update fused (sparseloco_aggregate_update): %.3f ms per step" % ms_fused,
-          file=sys.stderr, flush=True)
+    print("selections on the general radix path in one outer step at the timed state: %d of %d"
+          % (radix_selections, R * nch), file=sys.stderr, flush=True)
+    if ms_fused is not None:
+        print("with aggregate+update fused (sparseloco_aggregate_update): %.4f ms per step" % ms_fused,
+              file=sys.stderr, flush=True)
     if ms_batched is not None:
-        print("all replicas in one compress launch (sparseloco_compress_batch) + fused line 5: %.3f ms per step"
+        print("all replicas in one compress launch (sparseloco_compress_batch) + fused line 5: %.4f ms per step"
               % ms_batched, file=sys.stderr, flush=True)
+    if ms_graph is not None:
+        print("three-call step replayed from a HIP graph: %.4f ms per step (%.1f %% of HBM peak)"
+              % (ms_graph, 100 * gbs(total_bytes, ms_graph) / HBM_PEAK_GBS), file=sys.stderr, flush=True)
 
+    traffic, traffic_source = read_traffic(cfg["name"], args.layout)
     result = {
         "metric": "outer-step params/sec (compress+aggregate+update)",
         "value": n / (ms_step * 1e-3),
@@ -484,16 +577,22 @@ def main():
                                                          cfg["outer_lr"],
                                                          "64x64 tile chunks" if tiled else "flat 4096-element chunks"),
                    "n_params": n, "n_chunks": nch, "kappa": cfg["kappa"], "replicas": R,
+                   "timed_state": "outer steps %d..%d after the seeded inputs (theta_local fixed)"
+                                  % (args.warmup + 1, args.warmup + args.steps),
+                   "radix_path_selections_per_step": radix_selections, "selections_per_step": R * nch,
                    "step_algorithmic_bytes": total_bytes,
                    "step_frac_of_hbm_peak": gbs(total_bytes, ms_step) / HBM_PEAK_GBS,
                    "kernel_ms": {"compress": avg(ms_c), "aggregate": avg(ms_a), "outer_update": avg(ms_u)},
-                   "stream_reference_gbs": stream_ref_gbs,
-                   "fused_line5_ms_per_step": ms_fused, "fused_line5_params_per_s": n / (ms_fused * 1e-3),
+                   "kernel_gbs": {"compress": ach, "aggregate": gbs(b_a, avg(ms_a)), "outer_update": gbs(b_u, avg(ms_u))},
+                   "stream_reference_gbs": stream_ref_gbs, "stream_probe_gbs": probe_gbs,
+                   "fused_line5_ms_per_step": ms_fused,
+                   "fused_line5_params_per_s": None if ms_fused is None else n / (ms_fused * 1e-3),
                    "batched_ms_per_step": ms_batched,
                    "batched_params_per_s": None if ms_batched is None else n / (ms_batched * 1e-3),
-                   "batched_actual_bytes": (4 + 12 * R) * n + 8 * n + 2 * R * nch * (2 * cfg["kappa"] + 8)},
+                   "batched_actual_bytes": (4 + 12 * R) * n + 8 * n + 2 * R * nch * (2 * cfg["kappa"] + 8),
+                   "graph_replay_ms_per_step": ms_graph},
         "roofline": {"bound": "hbm", "kernel": "compress_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": read_traffic(cfg["name"]),
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": b_c},
     }
     if not args.no_cpu:

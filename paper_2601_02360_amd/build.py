@@ -14,7 +14,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "sparseloco.hip"), os.path.join(HERE, "csrc", "subspace.hip")]
+SOURCES = [os.path.join(HERE, "csrc", name) for name in ("sparseloco.hip", "subspace.hip", "stream_probe.hip")]
 LIB = os.path.join(HERE, "libsparseloco.so")
 
 HIPCC_FLAGS = [

@@ -33,9 +33,6 @@ constexpr int kChunk = SPLC_CHUNK;
 constexpr int kThreads = 256;            // one workgroup per chunk
 constexpr int kCandCap = 256;            // candidates the exact ranking handles (one per lane)
 constexpr int kFilterKappaMax = 256;     // the candidate filter needs kappa <= number of lanes
-constexpr int kSlots = 32;               // staging slots for pointer tables
-constexpr int kMaxReplicas = 1024;       // messages one aggregate call accepts
-constexpr int kMaxBatch = 64;            // replicas one compress_batch call accepts (and resets of aggregate_update)
 
 struct ChunkDesc {
     uint32_t tensor;                     // index into the pointer tables
@@ -296,8 +293,8 @@ __device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, ui
 template <int QUANT>
 __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x)[16], int tid, int lane, int wave,
                                                      uint32_t n_c, uint32_t pmask, uint32_t kappa, int force_radix,
-                                                     uint16_t* __restrict__ pairs_c, float* __restrict__ values_c,
-                                                     float* __restrict__ scales_c) {
+                                                     uint32_t* radix_counter, uint16_t* __restrict__ pairs_c,
+                                                     float* __restrict__ values_c, float* __restrict__ scales_c) {
     const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
     sh.cand[tid] = 0;
     if (tid < 2) sh.cand[kCandCap + tid] = 0;
@@ -376,7 +373,10 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
         }
     }
     __syncthreads();
-    if (!selected_by_filter) radix_select(sh, x, tid, pmask, kappa_c);
+    if (!selected_by_filter) {
+        radix_select(sh, x, tid, pmask, kappa_c);
+        if (radix_counter && tid == 0) atomicAdd(radix_counter, 1u);      // diagnostic: chunks on the general path
+    }
 
     // ---- final pass: selection predicate, output positions, quantise, pack, residual ----
     const uint64_t thr = sh.thr;
@@ -474,8 +474,8 @@ __device__ __forceinline__ void compress_body(SelectShared& sh, const ChunkDesc*
                                               const void* const* __restrict__ src_a,
                                               const void* const* __restrict__ src_b,
                                               float* const* __restrict__ ef_tab, float beta, uint32_t kappa,
-                                              int force_radix, uint16_t* __restrict__ pairs_out,
-                                              float* __restrict__ aux_out) {
+                                              int force_radix, uint32_t* radix_counter,
+                                              uint16_t* __restrict__ pairs_out, float* __restrict__ aux_out) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -490,8 +490,8 @@ __device__ __forceinline__ void compress_body(SelectShared& sh, const ChunkDesc*
     float x[16];
     if (VEC) load_fold_full<MODE>(pa, pb, pe, d, tid, beta, x);
     else load_fold_scalar<MODE>(pa, pb, pe, d, tid, beta, pmask, x);
-    select_quantise_pack<QUANT>(sh, x, tid, lane, wave, n_c, pmask, kappa, force_radix, pairs_out + c * kappa,
-                                aux_out + c * kappa, aux_out + 2 * c);
+    select_quantise_pack<QUANT>(sh, x, tid, lane, wave, n_c, pmask, kappa, force_radix, radix_counter,
+                                pairs_out + c * kappa, aux_out + c * kappa, aux_out + 2 * c);
     store_ef<VEC>(pe, d, tid, pmask, x);
 }
 
@@ -503,14 +503,16 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
                                                             const void* const* __restrict__ src_b,
                                                             float* const* __restrict__ ef_tab, float beta,
                                                             uint32_t kappa, int force_radix,
+                                                            uint32_t* radix_counter,
                                                             uint16_t* __restrict__ pairs_out,
                                                             float* __restrict__ aux_out) {
     __shared__ __align__(16) SelectShared sh;
     if (blockIdx.x >= n_gen)
-        compress_body<MODE, QUANT, true>(sh, chunks, src_a, src_b, ef_tab, beta, kappa, force_radix, pairs_out, aux_out);
+        compress_body<MODE, QUANT, true>(sh, chunks, src_a, src_b, ef_tab, beta, kappa, force_radix, radix_counter,
+                                         pairs_out, aux_out);
     else
-        compress_body<MODE, QUANT, false>(sh, chunks, src_a, src_b, ef_tab, beta, kappa, force_radix, pairs_out,
-                                          aux_out);
+        compress_body<MODE, QUANT, false>(sh, chunks, src_a, src_b, ef_tab, beta, kappa, force_radix, radix_counter,
+                                          pairs_out, aux_out);
 }
 
 // Lines 1-4 for R replicas that share theta_outer (several replicas simulated on one GPU): the
@@ -526,6 +528,7 @@ __device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so,
                                                                   const float* const* __restrict__ tl_tab,
                                                                   float* const* __restrict__ ef_tab, float beta,
                                                                   uint32_t kappa, int force_radix,
+                                                                  uint32_t* radix_counter,
                                                                   uint16_t* const* __restrict__ pairs_tab,
                                                                   float* const* __restrict__ aux_tab) {
     const int tid = threadIdx.x;
@@ -582,7 +585,7 @@ __device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so,
             }
         }
         float* aux_r = aux_tab[r];
-        select_quantise_pack<QUANT>(sh, x, t, t & 63, wave, n_c, pmask, kappa, force_radix,
+        select_quantise_pack<QUANT>(sh, x, t, t & 63, wave, n_c, pmask, kappa, force_radix, radix_counter,
                                     pairs_tab[r] + c * kappa, aux_r + c * kappa, aux_r + 2 * c);
         store_ef<VEC>(pe, d, t, pmask, x);
         __syncthreads();          // every lane is done with `sh` before the next replica re-initialises it
@@ -596,16 +599,17 @@ __global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDes
                                                                   const float* const* __restrict__ tl_tab,
                                                                   float* const* __restrict__ ef_tab, float beta,
                                                                   uint32_t kappa, int force_radix,
+                                                                  uint32_t* radix_counter,
                                                                   uint16_t* const* __restrict__ pairs_tab,
                                                                   float* const* __restrict__ aux_tab) {
     __shared__ __align__(16) SelectShared sh;
     __shared__ __align__(16) float so[kChunk];
     if (blockIdx.x >= n_gen)
         compress_batch_body<QUANT, true>(sh, so, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta, kappa,
-                                         force_radix, pairs_tab, aux_tab);
+                                         force_radix, radix_counter, pairs_tab, aux_tab);
     else
         compress_batch_body<QUANT, false>(sh, so, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta, kappa,
-                                          force_radix, pairs_tab, aux_tab);
+                                          force_radix, radix_counter, pairs_tab, aux_tab);
 }
 
 // Line 5, first half: sum of the decoded messages of one chunk into a dense LDS accumulator.
@@ -668,6 +672,9 @@ struct MessageBatch {
                     }
                     if (t < kappa_c) acc[idx] = __fadd_rn(acc[idx], q);
                 }
+                // The adds of replica r0 + i + 1 must follow those of replica r0 + i in program order (two replicas
+                // may hit the same index from different lanes): keep the compiler from moving LDS accesses across.
+                __builtin_amdgcn_wave_barrier();
             }
         }
     }
@@ -715,6 +722,7 @@ __device__ __forceinline__ void accumulate_chunk_any(float* acc, uint64_t c, uin
                 q = ar[c * kappa + t];
             }
             acc[idx] = __fadd_rn(acc[idx], q);
+            __builtin_amdgcn_wave_barrier();         // keeps the LDS accesses of successive rounds in program order
         }
     }
 }
@@ -863,6 +871,7 @@ struct sparseloco_plan {
     int kappa = 0;
     int quant = SPLC_QUANT_2BIT;
     int select = SPLC_SELECT_AUTO;
+    uint32_t* radix_counter = nullptr;   // diagnostic (sparseloco_plan_set_radix_counter), normally null
     int64_t n_chunks = 0;
     int64_t n_params = 0;
     std::vector<int64_t> numel;
@@ -871,49 +880,67 @@ struct sparseloco_plan {
     // fp32 and bf16]; every entry carries its chunk number.  The slow element-wise chunks come first so
     // that they overlap with the streaming ones instead of forming the tail of the launch.
     ChunkDesc* d_chunks = nullptr;
+    ChunkDesc* h_chunks = nullptr;       // pinned source of the asynchronous upload, kept until destroy
     int64_t n_gen_f32 = 0;               // entries of the first class
     int64_t n_gen_bf16 = 0;              // entries of the first two classes
-    // ring of staging slots for the per-call pointer tables
-    size_t slot_bytes = 0;
-    char* h_slots = nullptr;             // pinned host memory, kSlots * slot_bytes
-    char* d_slots = nullptr;             // device memory, kSlots * slot_bytes
-    hipEvent_t ev[kSlots] = {};
-    bool ev_used[kSlots] = {};
-    int next_slot = 0;
+};
+
+// n_sets lists of n_tensors device pointers, set-major, resident on the device.
+struct sparseloco_tensors {
+    int device = 0;
+    int n_tensors = 0;
+    int n_sets = 0;
+    int dtype = SPLC_F32;
+    void** d_table = nullptr;
+    void** h_table = nullptr;            // pinned source of the upload
+};
+
+// Message buffers of n_replicas replicas: device table [pairs: n_replicas][aux: n_replicas].
+struct sparseloco_messages {
+    int device = 0;
+    int n_replicas = 0;
+    int quant = SPLC_QUANT_2BIT;
+    int kappa = 0;
+    int64_t n_chunks = 0;
+    void** d_table = nullptr;
+    void** h_table = nullptr;
 };
 
 namespace {
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+bool finite(float v) { return v == v && v - v == 0.f; }
 
-// Reserve the next staging slot (waiting for the work that last used it) and return its host buffer.
-int slot_acquire(sparseloco_plan* plan, int* slot, char** host) {
-    int s = plan->next_slot;
-    if (plan->ev_used[s] && hipEventSynchronize(plan->ev[s]) != hipSuccess) return SPLC_EHIP;
-    plan->next_slot = (s + 1) % kSlots;
-    *slot = s;
-    *host = plan->h_slots + (size_t)s * plan->slot_bytes;
-    return SPLC_OK;
-}
-
-int slot_upload(sparseloco_plan* plan, int slot, size_t bytes, hipStream_t stream, char** dev) {
-    char* h = plan->h_slots + (size_t)slot * plan->slot_bytes;
-    char* dptr = plan->d_slots + (size_t)slot * plan->slot_bytes;
-    if (hipMemcpyAsync(dptr, h, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return SPLC_EHIP;
-    *dev = dptr;
-    return SPLC_OK;
-}
-
-int slot_release(sparseloco_plan* plan, int slot, hipStream_t stream) {
-    if (hipEventRecord(plan->ev[slot], stream) != hipSuccess) return SPLC_EHIP;
-    plan->ev_used[slot] = true;
-    return SPLC_OK;
-}
-
-int check_device(const sparseloco_plan* plan) {
+int current_device_is(int device) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return SPLC_EHIP;
-    return dev == plan->device ? SPLC_OK : SPLC_EPLAN;
+    return dev == device ? SPLC_OK : SPLC_EPLAN;
+}
+
+// A binding fits the plan: same device, same tensor count, the wanted element type, enough sets.
+int check_tensors(const sparseloco_plan* plan, const sparseloco_tensors* t, int dtype, int min_sets) {
+    if (!t) return SPLC_EINVAL;
+    if (t->device != plan->device || t->n_tensors != plan->n_tensors || t->dtype != dtype) return SPLC_EPLAN;
+    return t->n_sets >= min_sets ? SPLC_OK : SPLC_EINVAL;
+}
+int check_messages(const sparseloco_plan* plan, const sparseloco_messages* m, int min_replicas) {
+    if (!m) return SPLC_EINVAL;
+    if (m->device != plan->device || m->quant != plan->quant || m->kappa != plan->kappa || m->n_chunks != plan->n_chunks)
+        return SPLC_EPLAN;
+    return m->n_replicas >= min_replicas ? SPLC_OK : SPLC_EINVAL;
+}
+// Device table of set `set` of a binding (a single-set binding serves every set index).
+template <class T>
+T const* set_table(const sparseloco_tensors* t, int set) {
+    return reinterpret_cast<T const*>(t->d_table + (size_t)(t->n_sets == 1 ? 0 : set) * (size_t)t->n_tensors);
+}
+
+// A small table of device pointers: pinned host copy + device copy, uploaded asynchronously on `stream`.
+int upload_table(size_t n_ptrs, void*** h_out, void*** d_out) {
+    const size_t bytes = (n_ptrs ? n_ptrs : 1) * sizeof(void*);
+    if (hipHostMalloc(reinterpret_cast<void**>(h_out), bytes, hipHostMallocDefault) != hipSuccess) return SPLC_ENOMEM;
+    if (hipMalloc(reinterpret_cast<void**>(d_out), bytes) != hipSuccess) return SPLC_ENOMEM;
+    return SPLC_OK;
 }
 
 // Entries of the chunk table that take the element-wise path (they come first in the table).
@@ -926,7 +953,8 @@ void launch_compress(const sparseloco_plan* plan, const void* const* a, const vo
                      float beta, uint16_t* pairs_out, float* aux_out, hipStream_t stream) {
     hipLaunchKernelGGL((compress_kernel<MODE, QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
                        plan->d_chunks, gen_entries(plan, MODE == MODE_DIRECT_BF16), a, b, ef, beta,
-                       (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, pairs_out, aux_out);
+                       (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, plan->radix_counter, pairs_out,
+                       aux_out);
 }
 
 template <int QUANT>
@@ -935,7 +963,8 @@ void launch_compress_batch(const sparseloco_plan* plan, int n_replicas, const fl
                            float* const* aux, hipStream_t stream) {
     hipLaunchKernelGGL((compress_batch_kernel<QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
                        plan->d_chunks, gen_entries(plan, false), n_replicas, (uint32_t)plan->n_tensors, to, tl, ef,
-                       beta, (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, pairs, aux);
+                       beta, (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, plan->radix_counter, pairs,
+                       aux);
 }
 
 template <int QUANT, int UPDATE>
@@ -948,79 +977,39 @@ void launch_aggregate(const sparseloco_plan* plan, int n_replicas, const uint16_
 }
 
 // Shared by sparseloco_aggregate and sparseloco_aggregate_update.
-int aggregate_impl(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
-                          const float* const* aux, float* const* delta_bar_out, float* const* theta_outer,
-                          float outer_lr, bool update, int n_reset, float* const* const* theta_local_reset,
-                          void* stream) {
-    if (!plan || !pairs || !aux) return SPLC_EINVAL;
-    if (update ? !theta_outer : !delta_bar_out) return SPLC_EINVAL;
-    if (n_reset < 0 || n_reset > kMaxBatch || (n_reset > 0 && !theta_local_reset)) return SPLC_EINVAL;
-    for (int r = 0; r < n_reset; ++r) {
-        if (!theta_local_reset[r]) return SPLC_EINVAL;
-        for (int i = 0; i < plan->n_tensors; ++i) {
-            if (plan->numel[i] == 0) continue;
-            if (!theta_local_reset[r][i]) return SPLC_EINVAL;
-            if (!aligned(theta_local_reset[r][i], 4)) return SPLC_EALIGN;
-        }
-    }
-    if (n_replicas < 1 || n_replicas > kMaxReplicas) return SPLC_EINVAL;
-    if (!(outer_lr == outer_lr) || outer_lr - outer_lr != 0.f) return SPLC_EINVAL;
-    for (int r = 0; r < n_replicas; ++r) {
-        if (!pairs[r] || !aux[r]) return SPLC_EINVAL;
-        if (!aligned(pairs[r], 2) || !aligned(aux[r], 4)) return SPLC_EALIGN;
-    }
-    for (int i = 0; i < plan->n_tensors; ++i) {
-        if (plan->numel[i] == 0) continue;
-        if (delta_bar_out) {
-            if (!delta_bar_out[i]) return SPLC_EINVAL;
-            if (!aligned(delta_bar_out[i], 4)) return SPLC_EALIGN;
-        }
-        if (update) {
-            if (!theta_outer[i]) return SPLC_EINVAL;
-            if (!aligned(theta_outer[i], 4)) return SPLC_EALIGN;
-        }
-    }
-    int rc = check_device(plan);
+int aggregate_impl(const sparseloco_plan* plan, const sparseloco_messages* messages,
+                   const sparseloco_tensors* delta_bar_out, const sparseloco_tensors* theta_outer, float outer_lr,
+                   bool update, const sparseloco_tensors* reset, void* stream) {
+    if (!plan) return SPLC_EINVAL;
+    int rc = check_messages(plan, messages, 1);
     if (rc != SPLC_OK) return rc;
+    if (update ? !theta_outer : !delta_bar_out) return SPLC_EINVAL;
+    if (delta_bar_out && (rc = check_tensors(plan, delta_bar_out, SPLC_F32, 1)) != SPLC_OK) return rc;
+    if (update && (rc = check_tensors(plan, theta_outer, SPLC_F32, 1)) != SPLC_OK) return rc;
+    if (reset && (rc = check_tensors(plan, reset, SPLC_F32, 1)) != SPLC_OK) return rc;
+    if ((delta_bar_out && delta_bar_out->n_sets != 1) || (update && theta_outer->n_sets != 1)) return SPLC_EINVAL;
+    if (!finite(outer_lr)) return SPLC_EINVAL;
+    if ((rc = current_device_is(plan->device)) != SPLC_OK) return rc;
     if (plan->n_chunks == 0) return SPLC_OK;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int slot;
-    char* h;
-    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
-    const size_t nt = (size_t)plan->n_tensors, nr = (size_t)n_replicas;
-    void** tab = reinterpret_cast<void**>(h);
-    for (size_t r = 0; r < nr; ++r) {
-        tab[r] = const_cast<uint16_t*>(pairs[r]);
-        tab[nr + r] = const_cast<float*>(aux[r]);
-    }
-    for (size_t i = 0; i < nt; ++i) {
-        tab[2 * nr + i] = delta_bar_out ? delta_bar_out[i] : nullptr;
-        tab[2 * nr + nt + i] = update ? theta_outer[i] : nullptr;
-    }
-    for (size_t r = 0; r < (size_t)n_reset; ++r)
-        for (size_t i = 0; i < nt; ++i) tab[2 * nr + 2 * nt + r * nt + i] = theta_local_reset[r][i];
-    char* dtab;
-    if ((rc = slot_upload(plan, slot, (2 * nr + 2 * nt + (size_t)n_reset * nt) * sizeof(void*), st, &dtab)) !=
-        SPLC_OK)
-        return rc;
-    float* const* dreset = reinterpret_cast<float* const*>(dtab + (2 * nr + 2 * nt) * sizeof(void*));
-    const uint16_t* const* dp = reinterpret_cast<const uint16_t* const*>(dtab);
-    const float* const* dx = reinterpret_cast<const float* const*>(dtab + nr * sizeof(void*));
-    float* const* dout =
-        delta_bar_out ? reinterpret_cast<float* const*>(dtab + 2 * nr * sizeof(void*)) : nullptr;
-    float* const* dth = reinterpret_cast<float* const*>(dtab + (2 * nr + nt) * sizeof(void*));
+    const int nr = messages->n_replicas;
+    const uint16_t* const* dp = reinterpret_cast<const uint16_t* const*>(messages->d_table);
+    const float* const* dx = reinterpret_cast<const float* const*>(messages->d_table + nr);
+    float* const* dout = delta_bar_out ? set_table<float*>(delta_bar_out, 0) : nullptr;
+    float* const* dth = update ? set_table<float*>(theta_outer, 0) : nullptr;
+    float* const* dreset = reset ? set_table<float*>(reset, 0) : nullptr;
+    const int n_reset = reset ? reset->n_sets : 0;
     const bool q2 = plan->quant == SPLC_QUANT_2BIT;
     if (q2 && !update)
-        launch_aggregate<SPLC_QUANT_2BIT, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
+        launch_aggregate<SPLC_QUANT_2BIT, 0>(plan, nr, dp, dx, dout, dth, outer_lr, 0, dreset, st);
     else if (q2)
-        launch_aggregate<SPLC_QUANT_2BIT, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
+        launch_aggregate<SPLC_QUANT_2BIT, 1>(plan, nr, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
     else if (!update)
-        launch_aggregate<SPLC_QUANT_NONE, 0>(plan, n_replicas, dp, dx, dout, dth, outer_lr, 0, dreset, st);
+        launch_aggregate<SPLC_QUANT_NONE, 0>(plan, nr, dp, dx, dout, dth, outer_lr, 0, dreset, st);
     else
-        launch_aggregate<SPLC_QUANT_NONE, 1>(plan, n_replicas, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
-    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
-    return slot_release(plan, slot, st);
+        launch_aggregate<SPLC_QUANT_NONE, 1>(plan, nr, dp, dx, dout, dth, outer_lr, n_reset, dreset, st);
+    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
 // Chunk table of one tensor.  rows == 1 (or flat layout): runs of 4096 elements; otherwise 64 x 64 tiles
@@ -1062,12 +1051,10 @@ void append_chunks(std::vector<ChunkDesc>& table, uint32_t tensor, int64_t rows,
     }
 }
 
-int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled,
-                      int kappa, int quant_mode) {
-    if (!out) return SPLC_EINVAL;
-    *out = nullptr;
-    if (n_tensors < 1 || !cols || (tiled && !rows) || kappa < 1 || kappa > kChunk) return SPLC_EINVAL;
-    if (quant_mode != SPLC_QUANT_NONE && quant_mode != SPLC_QUANT_2BIT) return SPLC_EINVAL;
+// Validates the tensor list and counts its chunks; fills the table if one is given.
+int build_chunk_table(int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled, int64_t* n_chunks_out,
+                      int64_t* n_params_out, std::vector<ChunkDesc>* table) {
+    if (n_tensors < 1 || !cols || (tiled && !rows)) return SPLC_EINVAL;
     int64_t n_chunks = 0, n_params = 0;
     for (int i = 0; i < n_tensors; ++i) {
         const int64_t r = tiled ? rows[i] : 1, c = cols[i];
@@ -1082,6 +1069,47 @@ int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const 
         n_params += r * c;
     }
     if (n_chunks > 0x7FFFFFFF) return SPLC_EINVAL;      // one workgroup per chunk in a 1-D grid
+    *n_chunks_out = n_chunks;
+    *n_params_out = n_params;
+    if (!table) return SPLC_OK;
+    table->clear();
+    table->reserve((size_t)n_chunks);
+    for (int i = 0; i < n_tensors; ++i)
+        append_chunks(*table, (uint32_t)i, tiled ? rows[i] : 1, cols[i], tiled);
+    for (size_t k = 0; k < table->size(); ++k) (*table)[k].id = (uint32_t)k;
+    auto cls = [](const ChunkDesc& d) { return d.vec == 0 ? 0 : (d.vec == 1 ? 1 : 2); };
+    std::stable_sort(table->begin(), table->end(),
+                     [&](const ChunkDesc& a, const ChunkDesc& b) { return cls(a) < cls(b); });
+    if (tiled) {
+        // Workgroups go to the eight XCDs round-robin by number.  Neighbouring tiles of a tile row continue each
+        // other's 256-byte row segments (and share the cache lines on their common edge when the row length is
+        // no multiple of 32 floats), so each XCD is given a run of consecutive tiles (inside each class of the
+        // table) instead of every eighth one.  Only the order of processing changes: a chunk's number, and with
+        // it the place of its pairs in the message, is its `id`.
+        size_t start = 0;
+        while (start < table->size()) {
+            size_t end = start;
+            while (end < table->size() && cls((*table)[end]) == cls((*table)[start])) ++end;
+            const std::vector<ChunkDesc> seg(table->begin() + (ptrdiff_t)start, table->begin() + (ptrdiff_t)end);
+            size_t next = 0;
+            for (size_t r = 0; r < 8; ++r)
+                for (size_t pos = start + (r + 8 - start % 8) % 8; pos < end; pos += 8) (*table)[pos] = seg[next++];
+            start = end;
+        }
+    }
+    return SPLC_OK;
+}
+
+int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled, int chunk,
+               int kappa, int quant_mode, void* stream) {
+    if (!out) return SPLC_EINVAL;
+    *out = nullptr;
+    if (chunk != kChunk || kappa < 1 || kappa > kChunk) return SPLC_EINVAL;
+    if (quant_mode != SPLC_QUANT_NONE && quant_mode != SPLC_QUANT_2BIT) return SPLC_EINVAL;
+    int64_t n_chunks = 0, n_params = 0;
+    std::vector<ChunkDesc> table;
+    int rc = build_chunk_table(n_tensors, tiled ? rows : nullptr, cols, tiled, &n_chunks, &n_params, &table);
+    if (rc != SPLC_OK) return rc;
     sparseloco_plan* plan = new (std::nothrow) sparseloco_plan();
     if (!plan) return SPLC_ENOMEM;
     if (hipGetDevice(&plan->device) != hipSuccess) { delete plan; return SPLC_EHIP; }
@@ -1092,66 +1120,23 @@ int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const 
     plan->n_chunks = n_chunks;
     plan->n_params = n_params;
     plan->numel.resize((size_t)n_tensors);
-
-    std::vector<ChunkDesc> table;
-    table.reserve((size_t)n_chunks);
-    for (int i = 0; i < n_tensors; ++i) {
-        const int64_t r = tiled ? rows[i] : 1, c = cols[i];
-        plan->numel[(size_t)i] = r * c;
-        append_chunks(table, (uint32_t)i, r, c, tiled);
-    }
-    for (size_t k = 0; k < table.size(); ++k) table[k].id = (uint32_t)k;
-    std::stable_sort(table.begin(), table.end(), [](const ChunkDesc& a, const ChunkDesc& b) {
-        auto cls = [](const ChunkDesc& d) { return d.vec == 0 ? 0 : (d.vec == 1 ? 1 : 2); };
-        return cls(a) < cls(b);
-    });
+    for (int i = 0; i < n_tensors; ++i) plan->numel[(size_t)i] = (tiled ? rows[i] : 1) * cols[i];
     for (const ChunkDesc& cd : table) {
         plan->n_gen_f32 += cd.vec == 0;
         plan->n_gen_bf16 += cd.vec != 3;
     }
-    if (tiled) {
-        // Workgroups go to the eight XCDs round-robin by number.  Neighbouring tiles of a tile row continue each
-        // other's 256-byte row segments (and share the cache lines on their common edge when the row length is
-        // no multiple of 32 floats), so each XCD is given a run of consecutive tiles (inside each class of the
-        // table) instead of every eighth one.  Only the order of processing changes: a chunk's number, and with
-        // it the place of its pairs in the message, is its `id`.
-        size_t start = 0;
-        while (start < table.size()) {
-            size_t end = start;
-            auto cls = [](const ChunkDesc& d) { return d.vec == 0 ? 0 : (d.vec == 1 ? 1 : 2); };
-            while (end < table.size() && cls(table[end]) == cls(table[start])) ++end;
-            const std::vector<ChunkDesc> seg(table.begin() + (ptrdiff_t)start, table.begin() + (ptrdiff_t)end);
-            size_t next = 0;
-            for (size_t r = 0; r < 8; ++r)
-                for (size_t pos = start + (r + 8 - start % 8) % 8; pos < end; pos += 8) table[pos] = seg[next++];
-            start = end;
+    if (n_chunks > 0) {
+        const size_t bytes = (size_t)n_chunks * sizeof(ChunkDesc);
+        if (hipHostMalloc(reinterpret_cast<void**>(&plan->h_chunks), bytes, hipHostMallocDefault) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&plan->d_chunks), bytes) != hipSuccess) {
+            rc = SPLC_ENOMEM;
+        } else {
+            std::copy(table.begin(), table.end(), plan->h_chunks);
+            if (hipMemcpyAsync(plan->d_chunks, plan->h_chunks, bytes, hipMemcpyHostToDevice,
+                               static_cast<hipStream_t>(stream)) != hipSuccess)
+                rc = SPLC_EHIP;
         }
     }
-    int rc = SPLC_OK;
-    // largest pointer table of any call: aggregate (2 per replica + 2 per tensor), compress (3 per
-    // tensor), compress_batch ((1 + 2 R) per tensor + 2 R), aggregate_update with resets
-    size_t n_ptrs = 3 * (size_t)n_tensors + 2 * (size_t)kMaxReplicas;
-    const size_t n_batch = (1 + 2 * (size_t)kMaxBatch) * (size_t)n_tensors + 2 * (size_t)kMaxBatch;
-    if (n_batch > n_ptrs) n_ptrs = n_batch;
-    const size_t n_reset = 2 * (size_t)kMaxReplicas + (2 + (size_t)kMaxBatch) * (size_t)n_tensors;
-    if (n_reset > n_ptrs) n_ptrs = n_reset;
-    plan->slot_bytes = (n_ptrs * sizeof(void*) + 255) & ~(size_t)255;
-    if (n_chunks > 0 &&
-        hipMalloc(reinterpret_cast<void**>(&plan->d_chunks), (size_t)n_chunks * sizeof(ChunkDesc)) != hipSuccess)
-        rc = SPLC_ENOMEM;
-    if (rc == SPLC_OK && n_chunks > 0 &&
-        hipMemcpy(plan->d_chunks, table.data(), (size_t)n_chunks * sizeof(ChunkDesc), hipMemcpyHostToDevice) !=
-            hipSuccess)
-        rc = SPLC_EHIP;
-    if (rc == SPLC_OK &&
-        hipHostMalloc(reinterpret_cast<void**>(&plan->h_slots), kSlots * plan->slot_bytes, hipHostMallocDefault) !=
-            hipSuccess)
-        rc = SPLC_ENOMEM;
-    if (rc == SPLC_OK &&
-        hipMalloc(reinterpret_cast<void**>(&plan->d_slots), kSlots * plan->slot_bytes) != hipSuccess)
-        rc = SPLC_ENOMEM;
-    for (int s = 0; rc == SPLC_OK && s < kSlots; ++s)
-        if (hipEventCreateWithFlags(&plan->ev[s], hipEventDisableTiming) != hipSuccess) rc = SPLC_EHIP;
     if (rc != SPLC_OK) {
         sparseloco_plan_destroy(plan);
         return rc;
@@ -1164,31 +1149,26 @@ int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const 
 
 extern "C" {
 
-int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel, int kappa, int quant_mode) {
-    return plan_build(out, n_tensors, nullptr, numel, false, kappa, quant_mode);
+int sparseloco_plan_create(sparseloco_plan** out, int n_tensors, const int64_t* numel, int chunk, int kappa,
+                           int quant_mode, void* stream) {
+    return plan_build(out, n_tensors, nullptr, numel, false, chunk, kappa, quant_mode, stream);
 }
 
 int sparseloco_plan_create_2d(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols,
-                              int kappa, int quant_mode) {
-    return plan_build(out, n_tensors, rows, cols, true, kappa, quant_mode);
+                              int chunk, int kappa, int quant_mode, void* stream) {
+    return plan_build(out, n_tensors, rows, cols, true, chunk, kappa, quant_mode, stream);
 }
 
 void sparseloco_plan_destroy(sparseloco_plan* plan) {
     if (!plan) return;
-    for (int s = 0; s < kSlots; ++s) {
-        if (plan->ev[s]) {
-            if (plan->ev_used[s]) (void)hipEventSynchronize(plan->ev[s]);
-            (void)hipEventDestroy(plan->ev[s]);
-        }
-    }
-    if (plan->d_chunks) (void)hipFree(plan->d_chunks);
-    if (plan->d_slots) (void)hipFree(plan->d_slots);
-    if (plan->h_slots) (void)hipHostFree(plan->h_slots);
+    if (plan->d_chunks) (void)hipFree(plan->d_chunks);              // waits for the device
+    if (plan->h_chunks) (void)hipHostFree(plan->h_chunks);
     delete plan;
 }
 
 int64_t sparseloco_plan_num_chunks(const sparseloco_plan* plan) { return plan ? plan->n_chunks : SPLC_EINVAL; }
 int64_t sparseloco_plan_num_params(const sparseloco_plan* plan) { return plan ? plan->n_params : SPLC_EINVAL; }
+int sparseloco_plan_num_tensors(const sparseloco_plan* plan) { return plan ? plan->n_tensors : SPLC_EINVAL; }
 int sparseloco_plan_kappa(const sparseloco_plan* plan) { return plan ? plan->kappa : SPLC_EINVAL; }
 int sparseloco_plan_quant_mode(const sparseloco_plan* plan) { return plan ? plan->quant : SPLC_EINVAL; }
 int sparseloco_plan_layout(const sparseloco_plan* plan) { return plan ? plan->layout : SPLC_EINVAL; }
@@ -1199,52 +1179,153 @@ int sparseloco_plan_set_select(sparseloco_plan* plan, int select_mode) {
     return SPLC_OK;
 }
 
-int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype, const void* const* src_a,
-                        const void* const* src_b, float* const* ef, float beta, uint16_t* pairs_out,
-                        float* aux_out, void* stream) {
-    if (!plan || !src_a || !ef || !pairs_out || !aux_out) return SPLC_EINVAL;
-    int mode;
+int sparseloco_plan_set_radix_counter(sparseloco_plan* plan, uint32_t* device_counter) {
+    if (!plan || !aligned(device_counter, 4)) return SPLC_EINVAL;
+    plan->radix_counter = device_counter;
+    return SPLC_OK;
+}
+
+int64_t sparseloco_chunk_table(int n_tensors, const int64_t* rows, const int64_t* cols, int layout, void* out,
+                               int64_t capacity) {
+    if (layout != SPLC_LAYOUT_FLAT && layout != SPLC_LAYOUT_TILE64) return SPLC_EINVAL;
+    if (capacity < 0 || (capacity > 0 && !out)) return SPLC_EINVAL;
+    const bool tiled = layout == SPLC_LAYOUT_TILE64;
+    int64_t n_chunks = 0, n_params = 0;
+    std::vector<ChunkDesc> table;
+    std::vector<int64_t> flat;
+    if (!tiled && rows && cols && n_tensors >= 1) {               // flat layout: only the element counts matter
+        flat.resize((size_t)n_tensors);
+        for (int i = 0; i < n_tensors; ++i) {
+            if (rows[i] < 0 || cols[i] < 0 || (rows[i] > 0 && cols[i] > (int64_t)0x7FFFFFFFFFFFFFFF / rows[i]))
+                return SPLC_EINVAL;
+            flat[(size_t)i] = rows[i] * cols[i];
+        }
+        cols = flat.data();
+    }
+    int rc = build_chunk_table(n_tensors, tiled ? rows : nullptr, cols, tiled, &n_chunks, &n_params,
+                               out ? &table : nullptr);
+    if (rc != SPLC_OK) return rc;
+    if (out) {
+        const int64_t n = n_chunks < capacity ? n_chunks : capacity;
+        std::copy(table.begin(), table.begin() + (ptrdiff_t)n, static_cast<ChunkDesc*>(out));
+    }
+    return n_chunks;
+}
+
+int sparseloco_tensors_bind(sparseloco_tensors** out, const sparseloco_plan* plan, int n_sets,
+                            const void* const* ptrs, int dtype, void* stream) {
+    if (!out) return SPLC_EINVAL;
+    *out = nullptr;
+    if (!plan || !ptrs || n_sets < 1 || n_sets > SPLC_MAX_REPLICAS) return SPLC_EINVAL;
+    if (dtype != SPLC_F32 && dtype != SPLC_BF16) return SPLC_EINVAL;
+    const size_t nt = (size_t)plan->n_tensors, n = nt * (size_t)n_sets;
+    for (size_t i = 0; i < n; ++i) {
+        if (plan->numel[i % nt] == 0) continue;
+        if (!ptrs[i]) return SPLC_EINVAL;
+        if (!aligned(ptrs[i], 4)) return SPLC_EALIGN;             // for bf16 it keeps vector rows dword aligned
+    }
+    int rc = current_device_is(plan->device);
+    if (rc != SPLC_OK) return rc;
+    sparseloco_tensors* t = new (std::nothrow) sparseloco_tensors();
+    if (!t) return SPLC_ENOMEM;
+    t->device = plan->device;
+    t->n_tensors = plan->n_tensors;
+    t->n_sets = n_sets;
+    t->dtype = dtype;
+    if ((rc = upload_table(n, &t->h_table, &t->d_table)) == SPLC_OK) {
+        for (size_t i = 0; i < n; ++i) t->h_table[i] = plan->numel[i % nt] == 0 ? nullptr : const_cast<void*>(ptrs[i]);
+        if (hipMemcpyAsync(t->d_table, t->h_table, n * sizeof(void*), hipMemcpyHostToDevice,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+            rc = SPLC_EHIP;
+    }
+    if (rc != SPLC_OK) {
+        sparseloco_tensors_release(t);
+        return rc;
+    }
+    *out = t;
+    return SPLC_OK;
+}
+
+void sparseloco_tensors_release(sparseloco_tensors* t) {
+    if (!t) return;
+    if (t->d_table) (void)hipFree(t->d_table);                     // waits for the device
+    if (t->h_table) (void)hipHostFree(t->h_table);
+    delete t;
+}
+
+int sparseloco_messages_bind(sparseloco_messages** out, const sparseloco_plan* plan, int n_replicas,
+                             uint16_t* const* pairs, float* const* aux, void* stream) {
+    if (!out) return SPLC_EINVAL;
+    *out = nullptr;
+    if (!plan || !pairs || !aux || n_replicas < 1 || n_replicas > SPLC_MAX_REPLICAS) return SPLC_EINVAL;
+    for (int r = 0; r < n_replicas; ++r) {
+        if (plan->n_chunks == 0) continue;
+        if (!pairs[r] || !aux[r]) return SPLC_EINVAL;
+        if (!aligned(pairs[r], 2) || !aligned(aux[r], 4)) return SPLC_EALIGN;
+    }
+    int rc = current_device_is(plan->device);
+    if (rc != SPLC_OK) return rc;
+    sparseloco_messages* m = new (std::nothrow) sparseloco_messages();
+    if (!m) return SPLC_ENOMEM;
+    m->device = plan->device;
+    m->n_replicas = n_replicas;
+    m->quant = plan->quant;
+    m->kappa = plan->kappa;
+    m->n_chunks = plan->n_chunks;
+    const size_t nr = (size_t)n_replicas;
+    if ((rc = upload_table(2 * nr, &m->h_table, &m->d_table)) == SPLC_OK) {
+        for (size_t r = 0; r < nr; ++r) {
+            m->h_table[r] = pairs[r];
+            m->h_table[nr + r] = aux[r];
+        }
+        if (hipMemcpyAsync(m->d_table, m->h_table, 2 * nr * sizeof(void*), hipMemcpyHostToDevice,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+            rc = SPLC_EHIP;
+    }
+    if (rc != SPLC_OK) {
+        sparseloco_messages_release(m);
+        return rc;
+    }
+    *out = m;
+    return SPLC_OK;
+}
+
+void sparseloco_messages_release(sparseloco_messages* m) {
+    if (!m) return;
+    if (m->d_table) (void)hipFree(m->d_table);
+    if (m->h_table) (void)hipHostFree(m->h_table);
+    delete m;
+}
+
+int sparseloco_compress(const sparseloco_plan* plan, int delta_mode, const sparseloco_tensors* src_a,
+                        const sparseloco_tensors* src_b, const sparseloco_tensors* ef, int replica, float beta,
+                        uint16_t* pairs_out, float* aux_out, void* stream) {
+    if (!plan || !src_a || !ef || !pairs_out || !aux_out || replica < 0) return SPLC_EINVAL;
+    int mode, rc;
     if (delta_mode == SPLC_DELTA_FROM_PARAMS) {
-        if (src_dtype != SPLC_F32 || !src_b) return SPLC_EINVAL;
+        if (!src_b) return SPLC_EINVAL;
+        if ((rc = check_tensors(plan, src_a, SPLC_F32, 1)) != SPLC_OK) return rc;
+        if ((rc = check_tensors(plan, src_b, SPLC_F32, 1)) != SPLC_OK) return rc;
         mode = MODE_PARAMS_F32;
     } else if (delta_mode == SPLC_DELTA_DIRECT) {
         if (src_b) return SPLC_EINVAL;
-        if (src_dtype == SPLC_F32) mode = MODE_DIRECT_F32;
-        else if (src_dtype == SPLC_BF16) mode = MODE_DIRECT_BF16;
-        else return SPLC_EINVAL;
+        if ((rc = check_tensors(plan, src_a, src_a->dtype, 1)) != SPLC_OK) return rc;
+        mode = src_a->dtype == SPLC_BF16 ? MODE_DIRECT_BF16 : MODE_DIRECT_F32;
     } else {
         return SPLC_EINVAL;
     }
-    if (!(beta == beta) || beta - beta != 0.f) return SPLC_EINVAL;      // finite
-    const size_t src_align = 4;          // natural for fp32; for bf16 it keeps vector rows dword aligned
-    for (int i = 0; i < plan->n_tensors; ++i) {
-        if (plan->numel[i] == 0) continue;
-        if (!src_a[i] || !ef[i] || (mode == MODE_PARAMS_F32 && !src_b[i])) return SPLC_EINVAL;
-        if (!aligned(src_a[i], src_align) || !aligned(ef[i], 4) ||
-            (mode == MODE_PARAMS_F32 && !aligned(src_b[i], 4)))
-            return SPLC_EALIGN;
-    }
+    if ((rc = check_tensors(plan, ef, SPLC_F32, 1)) != SPLC_OK) return rc;
+    for (const sparseloco_tensors* t : {src_a, src_b, ef})
+        if (t && t->n_sets > 1 && replica >= t->n_sets) return SPLC_EINVAL;
+    if (!finite(beta)) return SPLC_EINVAL;
     if (!aligned(pairs_out, 2) || !aligned(aux_out, 4)) return SPLC_EALIGN;
-    int rc = check_device(plan);
-    if (rc != SPLC_OK) return rc;
+    if ((rc = current_device_is(plan->device)) != SPLC_OK) return rc;
     if (plan->n_chunks == 0) return SPLC_OK;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int slot;
-    char* h;
-    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
-    const size_t nt = (size_t)plan->n_tensors;
-    void** tab = reinterpret_cast<void**>(h);
-    for (size_t i = 0; i < nt; ++i) {
-        tab[i] = const_cast<void*>(src_a[i]);
-        tab[nt + i] = src_b ? const_cast<void*>(src_b[i]) : nullptr;
-        tab[2 * nt + i] = ef[i];
-    }
-    char* dtab;
-    if ((rc = slot_upload(plan, slot, 3 * nt * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
-    const void* const* da = reinterpret_cast<const void* const*>(dtab);
-    const void* const* db = reinterpret_cast<const void* const*>(dtab + nt * sizeof(void*));
-    float* const* de = reinterpret_cast<float* const*>(dtab + 2 * nt * sizeof(void*));
+    const void* const* da = set_table<const void*>(src_a, replica);
+    const void* const* db = src_b ? set_table<const void*>(src_b, replica) : nullptr;
+    float* const* de = set_table<float*>(ef, replica);
     const bool q2 = plan->quant == SPLC_QUANT_2BIT;
     switch (mode) {
         case MODE_PARAMS_F32:
@@ -1260,109 +1341,61 @@ int sparseloco_compress(sparseloco_plan* plan, int delta_mode, int src_dtype, co
             else launch_compress<MODE_DIRECT_BF16, SPLC_QUANT_NONE>(plan, da, db, de, beta, pairs_out, aux_out, st);
             break;
     }
-    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
-    return slot_release(plan, slot, st);
+    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
-int sparseloco_compress_batch(sparseloco_plan* plan, int n_replicas, const float* const* theta_outer,
-                              const float* const* const* theta_local, float* const* const* ef, float beta,
-                              uint16_t* const* pairs_out, float* const* aux_out, void* stream) {
-    if (!plan || !theta_outer || !theta_local || !ef || !pairs_out || !aux_out) return SPLC_EINVAL;
-    if (n_replicas < 1 || n_replicas > kMaxBatch) return SPLC_EINVAL;
-    if (!(beta == beta) || beta - beta != 0.f) return SPLC_EINVAL;
-    for (int r = 0; r < n_replicas; ++r) {
-        if (!theta_local[r] || !ef[r] || !pairs_out[r] || !aux_out[r]) return SPLC_EINVAL;
-        if (!aligned(pairs_out[r], 2) || !aligned(aux_out[r], 4)) return SPLC_EALIGN;
-    }
-    for (int i = 0; i < plan->n_tensors; ++i) {
-        if (plan->numel[i] == 0) continue;
-        if (!theta_outer[i]) return SPLC_EINVAL;
-        if (!aligned(theta_outer[i], 4)) return SPLC_EALIGN;
-        for (int r = 0; r < n_replicas; ++r) {
-            if (!theta_local[r][i] || !ef[r][i]) return SPLC_EINVAL;
-            if (!aligned(theta_local[r][i], 4) || !aligned(ef[r][i], 4)) return SPLC_EALIGN;
-        }
-    }
-    int rc = check_device(plan);
-    if (rc != SPLC_OK) return rc;
+int sparseloco_compress_batch(const sparseloco_plan* plan, int n_replicas, const sparseloco_tensors* theta_outer,
+                              const sparseloco_tensors* theta_local, const sparseloco_tensors* ef, float beta,
+                              const sparseloco_messages* messages_out, void* stream) {
+    if (!plan || n_replicas < 1 || n_replicas > SPLC_MAX_REPLICAS) return SPLC_EINVAL;
+    int rc;
+    if ((rc = check_tensors(plan, theta_outer, SPLC_F32, 1)) != SPLC_OK) return rc;
+    if (theta_outer->n_sets != 1) return SPLC_EINVAL;
+    if ((rc = check_tensors(plan, theta_local, SPLC_F32, n_replicas)) != SPLC_OK) return rc;
+    if ((rc = check_tensors(plan, ef, SPLC_F32, n_replicas)) != SPLC_OK) return rc;
+    if ((rc = check_messages(plan, messages_out, n_replicas)) != SPLC_OK) return rc;
+    if (!finite(beta)) return SPLC_EINVAL;
+    if ((rc = current_device_is(plan->device)) != SPLC_OK) return rc;
     if (plan->n_chunks == 0) return SPLC_OK;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int slot;
-    char* h;
-    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
-    const size_t nt = (size_t)plan->n_tensors, nr = (size_t)n_replicas;
-    void** tab = reinterpret_cast<void**>(h);
-    // [theta_outer: nt][theta_local: nr*nt][ef: nr*nt][pairs: nr][aux: nr]
-    for (size_t i = 0; i < nt; ++i) tab[i] = const_cast<float*>(theta_outer[i]);
-    for (size_t r = 0; r < nr; ++r) {
-        for (size_t i = 0; i < nt; ++i) {
-            tab[nt + r * nt + i] = const_cast<float*>(theta_local[r][i]);
-            tab[nt + nr * nt + r * nt + i] = ef[r][i];
-        }
-        tab[nt + 2 * nr * nt + r] = pairs_out[r];
-        tab[nt + 2 * nr * nt + nr + r] = aux_out[r];
-    }
-    char* dtab;
-    const size_t total = nt + 2 * nr * nt + 2 * nr;
-    if ((rc = slot_upload(plan, slot, total * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
-    const float* const* d_to = reinterpret_cast<const float* const*>(dtab);
-    const float* const* d_tl = reinterpret_cast<const float* const*>(dtab + nt * sizeof(void*));
-    float* const* d_ef = reinterpret_cast<float* const*>(dtab + (nt + nr * nt) * sizeof(void*));
-    uint16_t* const* d_pairs = reinterpret_cast<uint16_t* const*>(dtab + (nt + 2 * nr * nt) * sizeof(void*));
-    float* const* d_aux = reinterpret_cast<float* const*>(dtab + (nt + 2 * nr * nt + nr) * sizeof(void*));
+    const float* const* d_to = set_table<const float*>(theta_outer, 0);
+    const float* const* d_tl = reinterpret_cast<const float* const*>(theta_local->d_table);
+    float* const* d_ef = reinterpret_cast<float* const*>(ef->d_table);
+    uint16_t* const* d_pairs = reinterpret_cast<uint16_t* const*>(messages_out->d_table);
+    float* const* d_aux = reinterpret_cast<float* const*>(messages_out->d_table + messages_out->n_replicas);
     if (plan->quant == SPLC_QUANT_2BIT)
         launch_compress_batch<SPLC_QUANT_2BIT>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
     else
         launch_compress_batch<SPLC_QUANT_NONE>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
-    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
-    return slot_release(plan, slot, st);
+    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
-int sparseloco_aggregate(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
-                         const float* const* aux, float* const* delta_bar_out, void* stream) {
-    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, nullptr, 0.f, false, 0, nullptr, stream);
+int sparseloco_aggregate(const sparseloco_plan* plan, const sparseloco_messages* messages,
+                         const sparseloco_tensors* delta_bar_out, void* stream) {
+    return aggregate_impl(plan, messages, delta_bar_out, nullptr, 0.f, false, nullptr, stream);
 }
 
-int sparseloco_aggregate_update(sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
-                                const float* const* aux, float* const* theta_outer, float outer_lr,
-                                float* const* delta_bar_out, int n_reset, float* const* const* theta_local_reset,
+int sparseloco_aggregate_update(const sparseloco_plan* plan, const sparseloco_messages* messages,
+                                const sparseloco_tensors* theta_outer, float outer_lr,
+                                const sparseloco_tensors* delta_bar_out, const sparseloco_tensors* theta_local_reset,
                                 void* stream) {
-    return aggregate_impl(plan, n_replicas, pairs, aux, delta_bar_out, theta_outer, outer_lr, true, n_reset,
-                          theta_local_reset, stream);
+    return aggregate_impl(plan, messages, delta_bar_out, theta_outer, outer_lr, true, theta_local_reset, stream);
 }
 
-int sparseloco_outer_update(sparseloco_plan* plan, float* const* theta_outer, const float* const* delta_bar,
-                            float outer_lr, void* stream) {
-    if (!plan || !theta_outer || !delta_bar) return SPLC_EINVAL;
-    if (!(outer_lr == outer_lr) || outer_lr - outer_lr != 0.f) return SPLC_EINVAL;
-    for (int i = 0; i < plan->n_tensors; ++i) {
-        if (plan->numel[i] == 0) continue;
-        if (!theta_outer[i] || !delta_bar[i]) return SPLC_EINVAL;
-        if (!aligned(theta_outer[i], 4) || !aligned(delta_bar[i], 4)) return SPLC_EALIGN;
-    }
-    int rc = check_device(plan);
-    if (rc != SPLC_OK) return rc;
+int sparseloco_outer_update(const sparseloco_plan* plan, const sparseloco_tensors* theta_outer,
+                            const sparseloco_tensors* delta_bar, float outer_lr, void* stream) {
+    if (!plan) return SPLC_EINVAL;
+    int rc;
+    if ((rc = check_tensors(plan, theta_outer, SPLC_F32, 1)) != SPLC_OK) return rc;
+    if ((rc = check_tensors(plan, delta_bar, SPLC_F32, 1)) != SPLC_OK) return rc;
+    if (theta_outer->n_sets != 1 || delta_bar->n_sets != 1 || !finite(outer_lr)) return SPLC_EINVAL;
+    if ((rc = current_device_is(plan->device)) != SPLC_OK) return rc;
     if (plan->n_chunks == 0) return SPLC_OK;
-
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    int slot;
-    char* h;
-    if ((rc = slot_acquire(plan, &slot, &h)) != SPLC_OK) return rc;
-    const size_t nt = (size_t)plan->n_tensors;
-    void** tab = reinterpret_cast<void**>(h);
-    for (size_t i = 0; i < nt; ++i) {
-        tab[i] = theta_outer[i];
-        tab[nt + i] = const_cast<float*>(delta_bar[i]);
-    }
-    char* dtab;
-    if ((rc = slot_upload(plan, slot, 2 * nt * sizeof(void*), st, &dtab)) != SPLC_OK) return rc;
-    float* const* dth = reinterpret_cast<float* const*>(dtab);
-    const float* const* ddb = reinterpret_cast<const float* const*>(dtab + nt * sizeof(void*));
-    hipLaunchKernelGGL(outer_update_kernel, dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, st, plan->d_chunks,
-                       gen_entries(plan, false), dth, ddb, outer_lr);
-    if (hipGetLastError() != hipSuccess) return SPLC_EHIP;
-    return slot_release(plan, slot, st);
+    hipLaunchKernelGGL(outer_update_kernel, dim3((unsigned)plan->n_chunks), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), plan->d_chunks, gen_entries(plan, false),
+                       set_table<float*>(theta_outer, 0), set_table<const float*>(delta_bar, 0), outer_lr);
+    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
 const char* sparseloco_strerror(int status) {
@@ -1372,7 +1405,7 @@ const char* sparseloco_strerror(int status) {
         case SPLC_EALIGN: return "tensor pointer not sufficiently aligned";
         case SPLC_ENOMEM: return "allocation failed";
         case SPLC_EHIP: return "HIP runtime call failed";
-        case SPLC_EPLAN: return "call does not match the plan";
+        case SPLC_EPLAN: return "call does not match the plan or a binding";
         case SPLC_ETOOBIG: return "problem exceeds the fixed workspace of this call";
         default: return "unknown status";
     }

@@ -744,14 +744,12 @@ bool narrow_applies(int d, int k, const HighRank& h) {
     return d % 32 == 0 && k <= (tables == 2 ? 16 : 32);
 }
 
-int g_matmul_mode = SPLC_MATMUL_FP32;      // process-wide, set by sparseloco_set_matmul_mode
-
 template <int TM_, int TN_, bool B_NK, class Pro, class Epi>
 void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
-                      hipStream_t st) {
+                      int matmul, hipStream_t st) {
     const int64_t row_blocks = ((int64_t)(M + TM_ - 1) / TM_ + 7) / 8 * 8;
     dim3 grid((unsigned)(row_blocks * ((N + TN_ - 1) / TN_)));
-    if (g_matmul_mode == SPLC_MATMUL_BF16X3)
+    if (matmul == SPLC_MATMUL_BF16X3)
         hipLaunchKernelGGL((gemm_kernel<MATH_BF16X3, TM_, TN_, B_NK, Pro, Epi>), grid, dim3(kThreads), 0, st, A, lda, B,
                            ldb, M, N, K, pro, epi);
     else
@@ -767,60 +765,61 @@ void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, 
 //            with another's products); beyond that the reconstruction (light_epilogue: one store per
 //            output) still prefers 64 rows;
 //   with split-bf16 products (measured separately): see below.
-template <bool B_NK, class Pro, class Epi>
-void launch_gemm(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
-                 hipStream_t st, bool light_epilogue = false) {
+struct GemmTile { bool tall, wide; };
+GemmTile choose_gemm_tile(bool b_nk, int M, int N, int K, bool light_epilogue, int matmul) {
     auto groups = [&](int tm, int tn) { return (int64_t)((M + tm - 1) / tm) * ((N + tn - 1) / tn); };
     bool wide = ((N + 63) / 64) % 2 == 0;
     bool tall;
-    if (g_matmul_mode == SPLC_MATMUL_BF16X3) {
+    if (matmul == SPLC_MATMUL_BF16X3) {
         // split operands: a tile's matrix work is a third as long and splitting costs per staged value, so the
         // large tile, which stages fewest values per product, wins wherever it leaves 1.5 groups per compute unit
-        tall = B_NK || groups(128, wide ? 128 : 64) >= 3 * 128;
-    } else if (B_NK && K <= 192) {
+        tall = b_nk || groups(128, wide ? 128 : 64) >= 3 * 128;
+    } else if (b_nk && K <= 192) {
         wide = tall = false;
     } else if (light_epilogue) {
         tall = false;
     } else {
         tall = groups(128, wide ? 128 : 64) >= 2 * 256;
     }
-    if (tall && wide) launch_gemm_tile<128, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
-    else if (tall) launch_gemm_tile<128, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
-    else if (wide) launch_gemm_tile<64, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
-    else launch_gemm_tile<64, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, st);
+    return GemmTile{tall, wide};
 }
+template <bool B_NK, class Pro, class Epi>
+void launch_gemm(const float* A, int64_t lda, const float* B, int64_t ldb, int M, int N, int K, Pro pro, Epi epi,
+                 int matmul, hipStream_t st, bool light_epilogue = false) {
+    const GemmTile t = choose_gemm_tile(B_NK, M, N, K, light_epilogue, matmul);
+    if (t.tall && t.wide) launch_gemm_tile<128, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, matmul, st);
+    else if (t.tall) launch_gemm_tile<128, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, matmul, st);
+    else if (t.wide) launch_gemm_tile<64, 128, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, matmul, st);
+    else launch_gemm_tile<64, 64, B_NK>(A, lda, B, ldb, M, N, K, pro, epi, matmul, st);
+}
+
+bool valid_matmul(int matmul) { return matmul == SPLC_MATMUL_FP32 || matmul == SPLC_MATMUL_BF16X3; }
 
 bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
 
 }  // namespace
 
-extern "C" int sparseloco_set_matmul_mode(int mode) {
-    if (mode != SPLC_MATMUL_FP32 && mode != SPLC_MATMUL_BF16X3) return SPLC_EINVAL;
-    g_matmul_mode = mode;
-    return SPLC_OK;
-}
-
-extern "C" int sparseloco_get_matmul_mode(void) { return g_matmul_mode; }
-
 namespace {
 
 // Both passes of the re-projection with the coefficients in `coeff_ws` (vocab * k floats of device memory).
 int reproject_impl(float* t_s, float* t_perp, const float* u, float* coeff_ws, int64_t vocab, int d, int k,
-                   hipStream_t st) {
+                   int matmul, hipStream_t st) {
     const int M = (int)vocab;
     // pass 1: coeff = T_S U            (M x k) = (M x d)(d x k)
     if (narrow_applies(d, k, HighRank{nullptr, nullptr, 0, nullptr, 1, (int64_t)d}))
         launch_project_narrow(t_s, HighRank{nullptr, nullptr, 0, nullptr, 1, (int64_t)d}, u, coeff_ws, M, d, k, st);
     else
-        launch_gemm<false>(t_s, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k}, st);
+        launch_gemm<false>(t_s, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k}, matmul,
+                           st);
     // pass 2: Pi = coeff U^T           (M x d) = (M x k)(k x d), U given as d x k = the N x K form
     launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, UpdateEmbedding{t_s, t_perp, (int64_t)d},
-                      st);
+                      matmul, st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
-int check_reproject_args(const float* t_s, const float* t_perp, const float* u, int64_t vocab, int d, int k) {
-    if (!t_s || !t_perp || !u) return SPLC_EINVAL;
+int check_reproject_args(const float* t_s, const float* t_perp, const float* u, int64_t vocab, int d, int k,
+                         int matmul) {
+    if (!t_s || !t_perp || !u || !valid_matmul(matmul)) return SPLC_EINVAL;
     if (vocab < 0 || vocab > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d) return SPLC_EINVAL;
     if (!aligned4(t_s) || !aligned4(t_perp) || !aligned4(u)) return SPLC_EALIGN;
     return SPLC_OK;
@@ -853,25 +852,25 @@ int scratch_of(float** out) {
 }  // namespace
 
 extern "C" int sparseloco_reproject_embedding(float* t_s, float* t_perp, const float* u, float* coeff_ws,
-                                              int64_t vocab, int d, int k, void* stream) {
+                                              int64_t vocab, int d, int k, int matmul, void* stream) {
     if (!coeff_ws) return SPLC_EINVAL;
-    int rc = check_reproject_args(t_s, t_perp, u, vocab, d, k);
+    int rc = check_reproject_args(t_s, t_perp, u, vocab, d, k, matmul);
     if (rc != SPLC_OK) return rc;
     if (!aligned4(coeff_ws)) return SPLC_EALIGN;
     if (vocab == 0) return SPLC_OK;
-    return reproject_impl(t_s, t_perp, u, coeff_ws, vocab, d, k, static_cast<hipStream_t>(stream));
+    return reproject_impl(t_s, t_perp, u, coeff_ws, vocab, d, k, matmul, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int sparseloco_reproject_embedding_noalloc(float* t_s, float* t_perp, const float* u, int64_t vocab, int d,
-                                                      int k, void* stream) {
-    int rc = check_reproject_args(t_s, t_perp, u, vocab, d, k);
+                                                      int k, int matmul, void* stream) {
+    int rc = check_reproject_args(t_s, t_perp, u, vocab, d, k, matmul);
     if (rc != SPLC_OK) return rc;
     if (vocab * (int64_t)k > (int64_t)SPLC_NOALLOC_MAX_COEFF) return SPLC_ETOOBIG;
     if (vocab == 0) return SPLC_OK;
     float* ws = nullptr;
     if ((rc = scratch_of(&ws)) != SPLC_OK) return rc;
     // Nothing has to start at zero: pass 1 writes every coefficient that pass 2 reads.
-    return reproject_impl(t_s, t_perp, u, ws, vocab, d, k, static_cast<hipStream_t>(stream));
+    return reproject_impl(t_s, t_perp, u, ws, vocab, d, k, matmul, static_cast<hipStream_t>(stream));
 }
 
 namespace {
@@ -884,10 +883,32 @@ int check_high_rank(const float* t_perp, const int32_t* token_ids, int vocab, co
 }
 }  // namespace
 
+extern "C" int sparseloco_subspace_kernel_choice(int op, int64_t rows, int d, int k, int tables, int matmul) {
+    if (rows < 1 || rows > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d || tables < 0 || tables > 2 || !valid_matmul(matmul))
+        return SPLC_EINVAL;
+    const int M = (int)rows;
+    const float* const some = reinterpret_cast<const float*>(&op);      // only tested for being non-null
+    GemmTile t;
+    switch (op) {
+        case SPLC_OP_PROJECT:
+        case SPLC_OP_REPROJECT_PASS1: {
+            const int n_tab = op == SPLC_OP_PROJECT ? tables : 0;
+            const HighRank h{n_tab >= 1 ? some : nullptr, nullptr, 0, n_tab >= 2 ? some : nullptr, 1, (int64_t)d};
+            if (narrow_applies(d, k, h)) return 16 * 256 + (k <= 16 ? 16 : 32);
+            t = choose_gemm_tile(false, M, k, d, false, matmul);
+            break;
+        }
+        case SPLC_OP_RECONSTRUCT: t = choose_gemm_tile(true, M, d, k, true, matmul); break;
+        case SPLC_OP_REPROJECT_PASS2: t = choose_gemm_tile(true, M, d, k, false, matmul); break;
+        default: return SPLC_EINVAL;
+    }
+    return (t.tall ? 128 : 64) * 256 + (t.wide ? 128 : 64);
+}
+
 extern "C" int sparseloco_subspace_project(const float* x, const float* t_perp, const int32_t* token_ids, int vocab,
                                            const float* pos_embed, int seq_len, const float* u, float* x_tilde,
-                                           int64_t rows, int d, int k, void* stream) {
-    if (!x || !u || !x_tilde) return SPLC_EINVAL;
+                                           int64_t rows, int d, int k, int matmul, void* stream) {
+    if (!x || !u || !x_tilde || !valid_matmul(matmul)) return SPLC_EINVAL;
     if (rows < 0 || rows > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d) return SPLC_EINVAL;
     int rc = check_high_rank(t_perp, token_ids, vocab, pos_embed, seq_len);
     if (rc != SPLC_OK) return rc;
@@ -900,22 +921,22 @@ extern "C" int sparseloco_subspace_project(const float* x, const float* t_perp, 
         launch_project_narrow(x, h, u, x_tilde, M, d, k, st);
     } else if (t_perp && pos_embed)
         launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank<true, true>{h, {nullptr, nullptr}},
-                           StoreCoeff{x_tilde, (int64_t)k}, st);
+                           StoreCoeff{x_tilde, (int64_t)k}, matmul, st);
     else if (t_perp)
         launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank<true, false>{h, {nullptr, nullptr}},
-                           StoreCoeff{x_tilde, (int64_t)k}, st);
+                           StoreCoeff{x_tilde, (int64_t)k}, matmul, st);
     else if (pos_embed)
         launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, SubtractHighRank<false, true>{h, {nullptr, nullptr}},
-                           StoreCoeff{x_tilde, (int64_t)k}, st);
+                           StoreCoeff{x_tilde, (int64_t)k}, matmul, st);
     else
-        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{x_tilde, (int64_t)k}, st);
+        launch_gemm<false>(x, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{x_tilde, (int64_t)k}, matmul, st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
 extern "C" int sparseloco_subspace_reconstruct(const float* x_tilde, const float* t_perp, const int32_t* token_ids,
                                                int vocab, const float* pos_embed, int seq_len, const float* u,
-                                               float* x_hat, int64_t rows, int d, int k, void* stream) {
-    if (!x_tilde || !u || !x_hat) return SPLC_EINVAL;
+                                               float* x_hat, int64_t rows, int d, int k, int matmul, void* stream) {
+    if (!x_tilde || !u || !x_hat || !valid_matmul(matmul)) return SPLC_EINVAL;
     if (rows < 0 || rows > 0x7FFFFFFF - TM || d < 1 || k < 1 || k > d) return SPLC_EINVAL;
     int rc = check_high_rank(t_perp, token_ids, vocab, pos_embed, seq_len);
     if (rc != SPLC_OK) return rc;
@@ -925,16 +946,16 @@ extern "C" int sparseloco_subspace_reconstruct(const float* x_tilde, const float
     const HighRank h{t_perp, token_ids, vocab, pos_embed, seq_len > 0 ? seq_len : 1, (int64_t)d};
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (t_perp && pos_embed)
-        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<true, true>{h, x_hat}, st,
-                          true);
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<true, true>{h, x_hat},
+                          matmul, st, true);
     else if (t_perp)
-        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<true, false>{h, x_hat}, st,
-                          true);
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<true, false>{h, x_hat},
+                          matmul, st, true);
     else if (pos_embed)
-        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<false, true>{h, x_hat}, st,
-                          true);
+        launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<false, true>{h, x_hat},
+                          matmul, st, true);
     else
         launch_gemm<true>(x_tilde, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, AddHighRank<false, false>{h, x_hat},
-                          st, true);
+                          matmul, st, true);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }

@@ -130,6 +130,16 @@ def replica_inputs(workload: int, tensor: int, replica: int, theta_o: torch.Tens
     return theta_l, None, (ef if outer_step == 0 else None)
 
 
+def orthonormal_basis(d: int, k: int, seed: int, device="cpu") -> torch.Tensor:
+    """A seeded random d x k fp32 matrix with orthonormal columns (the fixed random basis U of section 2.2):
+    Gaussian draw, QR in float64 on the host, signs fixed so that the result is reproducible."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed))
+    q, r = torch.linalg.qr(torch.randn(d, k, generator=g, dtype=torch.float64))
+    q = q * torch.sign(torch.diagonal(r))[None, :]
+    return q.to(torch.float32).contiguous().to(device)
+
+
 class ReplicaSet:
     """All inputs of a workload resident on one device: theta_outer, and per
     replica theta_local (or bf16 delta) and the error-feedback buffer."""

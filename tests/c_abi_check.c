@@ -69,17 +69,27 @@ int main(void) {
     }
     /* GPU path */
     sparseloco_plan* plan = NULL;
-    SPLCHECK(sparseloco_plan_create(&plan, N_TENSORS, numel, KAPPA, SPLC_QUANT_2BIT));
+    SPLCHECK(sparseloco_plan_create(&plan, N_TENSORS, numel, SPLC_CHUNK, KAPPA, SPLC_QUANT_2BIT, NULL));
     if (sparseloco_plan_num_chunks(plan) != n_chunks) { fprintf(stderr, "chunk count mismatch\n"); return 4; }
     uint16_t* d_pairs[R]; float* d_scales[R];
     for (int r = 0; r < R; ++r) {
         HIPCHECK(hipMalloc((void**)&d_pairs[r], (size_t)n_chunks * KAPPA * 2));
         HIPCHECK(hipMalloc((void**)&d_scales[r], (size_t)n_chunks * 2 * 4));
-        SPLCHECK(sparseloco_compress(plan, SPLC_DELTA_FROM_PARAMS, SPLC_F32, (const void* const*)d_to,
-                                     (const void* const*)d_tl[r], d_ef[r], 0.95f, d_pairs[r], d_scales[r], NULL));
     }
-    SPLCHECK(sparseloco_aggregate(plan, R, (const uint16_t* const*)d_pairs, (const float* const*)d_scales, d_db, NULL));
-    SPLCHECK(sparseloco_outer_update(plan, d_to, (const float* const*)d_db, 1.0f, NULL));
+    /* bind the tensor lists once: the shared parameters and the mean as single sets, the replicas' local
+       parameters and error-feedback buffers as R sets each, the R messages */
+    sparseloco_tensors *b_to = NULL, *b_db = NULL, *b_tl = NULL, *b_ef = NULL;
+    sparseloco_messages* b_msg = NULL;
+    SPLCHECK(sparseloco_tensors_bind(&b_to, plan, 1, (const void* const*)d_to, SPLC_F32, NULL));
+    SPLCHECK(sparseloco_tensors_bind(&b_db, plan, 1, (const void* const*)d_db, SPLC_F32, NULL));
+    SPLCHECK(sparseloco_tensors_bind(&b_tl, plan, R, (const void* const*)&d_tl[0][0], SPLC_F32, NULL));
+    SPLCHECK(sparseloco_tensors_bind(&b_ef, plan, R, (const void* const*)&d_ef[0][0], SPLC_F32, NULL));
+    SPLCHECK(sparseloco_messages_bind(&b_msg, plan, R, d_pairs, d_scales, NULL));
+    for (int r = 0; r < R; ++r)
+        SPLCHECK(sparseloco_compress(plan, SPLC_DELTA_FROM_PARAMS, b_to, b_tl, b_ef, r, 0.95f, d_pairs[r], d_scales[r],
+                                     NULL));
+    SPLCHECK(sparseloco_aggregate(plan, b_msg, b_db, NULL));
+    SPLCHECK(sparseloco_outer_update(plan, b_to, b_db, 1.0f, NULL));
     HIPCHECK(hipDeviceSynchronize());
 
     /* oracle */
@@ -122,6 +132,9 @@ int main(void) {
         for (int64_t i = 0; i < numel[t]; ++i) { if (a[i] != h_db[t][i]) ++bad; if (b[i] != h_to[t][i]) ++bad; }
         free(a); free(b);
     }
+    sparseloco_messages_release(b_msg);
+    sparseloco_tensors_release(b_to); sparseloco_tensors_release(b_db);
+    sparseloco_tensors_release(b_tl); sparseloco_tensors_release(b_ef);
     sparseloco_plan_destroy(plan);
     if (bad) { fprintf(stderr, "%ld mismatches\n", bad); return 1; }
     printf("c_abi_check: %d tensors, %lld chunks, %d replicas: GPU library and oracle agree\n", N_TENSORS,

@@ -89,45 +89,52 @@ def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AU
     """fused: None = aggregate then outer_update; "with_mean" / "no_mean" = sparseloco_aggregate_update
     with / without the dense mean output (without it, the returned mean is recomputed by a separate
     sparseloco_aggregate call, which the fused call must agree with anyway)."""
-    plan = B.Plan(case.shapes if case.shapes is not None else case.numels, kappa, quant,
-                  tiled=case.shapes is not None)
-    plan.set_select(select)
-    th = [_dev(x) for x in case.theta_outer]
-    ef = [[_dev(x) for x in r] for r in case.ef]
-    tl = None if case.theta_local is None else [[_dev(x) for x in r] for r in case.theta_local]
-    out = []
     ctx = torch.cuda.stream(stream) if stream is not None else torch.cuda.stream(torch.cuda.current_stream())
+    out = []
     with ctx:
+        plan = B.Plan(case.shapes if case.shapes is not None else case.numels, kappa, quant,
+                      tiled=case.shapes is not None)
+        plan.set_select(select)
+        th = [_dev(x) for x in case.theta_outer]
+        ef = [[_dev(x) for x in r] for r in case.ef]
+        tl = None if case.theta_local is None else [[_dev(x) for x in r] for r in case.theta_local]
+        b_th, b_ef = plan.bind(th), plan.bind(ef)
+        b_tl = None if tl is None else plan.bind(tl)
         for step in range(outer_steps):
             msgs = [plan.message_buffers() for _ in range(case.R)]
             for p, a in msgs:                       # poison: the library must overwrite everything
                 p.fill_(0x5A5A)
                 a.fill_(float("nan"))
+            b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
             if batch:
-                B.sparseloco_compress_batch(plan, th, tl, ef, [m[0] for m in msgs], [m[1] for m in msgs], beta)
+                B.sparseloco_compress_batch(plan, b_th, b_tl, b_ef, b_msgs, beta)
             for r in range(case.R if not batch else 0):
                 p, a = msgs[r]
                 if case.delta is not None:
                     src = case.delta[r] if deltas_per_step is None else deltas_per_step[step][r]
                     d = [_dev(x) for x in src]
-                    B.sparseloco_compress(plan, ef[r], p, a, beta, delta=d)
+                    B.sparseloco_compress(plan, b_ef, p, a, beta, delta=d, replica=r)
                 else:
-                    B.sparseloco_compress(plan, ef[r], p, a, beta, theta_outer=th, theta_local=tl[r])
+                    B.sparseloco_compress(plan, b_ef, p, a, beta, theta_outer=b_th, theta_local=b_tl, replica=r)
             dbar = [torch.full((n,), float("nan"), device="cuda") for n in case.numels]
+            b_dbar = plan.bind(dbar)
             if fused is None:
-                B.sparseloco_aggregate(plan, [m[0] for m in msgs], [m[1] for m in msgs], dbar)
-                B.sparseloco_outer_update(plan, th, dbar, lr)
+                B.sparseloco_aggregate(plan, b_msgs, b_dbar)
+                B.sparseloco_outer_update(plan, b_th, b_dbar, lr)
             elif fused == "with_mean":
-                B.sparseloco_aggregate_update(plan, [m[0] for m in msgs], [m[1] for m in msgs], th, lr,
-                                              delta_bar_out=dbar)
+                B.sparseloco_aggregate_update(plan, b_msgs, b_th, lr, delta_bar_out=b_dbar)
             else:
-                B.sparseloco_aggregate_update(plan, [m[0] for m in msgs], [m[1] for m in msgs], th, lr)
-                B.sparseloco_aggregate(plan, [m[0] for m in msgs], [m[1] for m in msgs], dbar)
+                B.sparseloco_aggregate_update(plan, b_msgs, b_th, lr)
+                B.sparseloco_aggregate(plan, b_msgs, b_dbar)
             torch.cuda.synchronize()
             out.append(dict(pairs=[to_np(m[0]) for m in msgs], aux=[to_np(m[1]) for m in msgs],
                             ef=[[to_np(x) for x in r] for r in ef], dbar=[to_np(x) for x in dbar],
                             theta=[to_np(x) for x in th]))
-    plan.close()
+            b_msgs.close(), b_dbar.close()
+        for b in (b_th, b_ef, b_tl):
+            if b is not None:
+                b.close()
+        plan.close()
     return out
 
 

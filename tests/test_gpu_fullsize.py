@@ -107,6 +107,8 @@ def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1
     dbar = [torch.empty(n, device="cuda") for n in rs.numels]
     got, deltas_per_step = [], []
     tl0 = None
+    b_theta, b_dbar, b_ef = plan.bind(rs.theta_outer), plan.bind(dbar), plan.bind(rs.ef)
+    b_tl = None if rs.direct else plan.bind(rs.theta_local)
     for step in range(outer_steps):
         if rs.direct:
             if step > 0:
@@ -117,15 +119,17 @@ def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1
         elif step == 0:
             tl0 = [gather_(rs.theta_local[r], picks) for r in range(R)]
         msgs = [plan.message_buffers() for _ in range(R)]
+        b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
         for r in range(R):
             if rs.direct:
-                B.sparseloco_compress(plan, rs.ef[r], msgs[r][0], msgs[r][1], cfg["beta"], delta=rs.delta[r])
+                B.sparseloco_compress(plan, b_ef, msgs[r][0], msgs[r][1], cfg["beta"], delta=rs.delta[r], replica=r)
             else:
-                B.sparseloco_compress(plan, rs.ef[r], msgs[r][0], msgs[r][1], cfg["beta"],
-                                      theta_outer=rs.theta_outer, theta_local=rs.theta_local[r])
-        B.sparseloco_aggregate(plan, [m[0] for m in msgs], [m[1] for m in msgs], dbar)
-        B.sparseloco_outer_update(plan, rs.theta_outer, dbar, cfg["outer_lr"])
+                B.sparseloco_compress(plan, b_ef, msgs[r][0], msgs[r][1], cfg["beta"],
+                                      theta_outer=b_theta, theta_local=b_tl, replica=r)
+        B.sparseloco_aggregate(plan, b_msgs, b_dbar)
+        B.sparseloco_outer_update(plan, b_theta, b_dbar, cfg["outer_lr"])
         torch.cuda.synchronize()
+        b_msgs.close()
         for r in (0, R - 1):
             if not tiled:
                 all_chunk_properties(plan, msgs[r], rs.numels, kappa)
@@ -201,7 +205,7 @@ def test_one_tensor_with_more_than_2_31_elements():
     msg = plan.message_buffers()
     dbar = torch.empty(n, device="cuda")
     B.sparseloco_compress(plan, [ef], msg[0], msg[1], 0.95, theta_outer=[theta_o], theta_local=[theta_l])
-    B.sparseloco_aggregate(plan, [msg[0]], [msg[1]], [dbar])
+    B.sparseloco_aggregate(plan, [msg[0]], [dbar], aux=[msg[1]])
     B.sparseloco_outer_update(plan, [theta_o], [dbar], 1.0)
     torch.cuda.synchronize()
     all_chunk_properties(plan, msg, [n], kappa)

@@ -81,7 +81,7 @@ def test_four_byte_aligned_views():
     plan = binding.Plan([n], 32)
     p, a = plan.message_buffers()
     binding.sparseloco_compress(plan, [views[2]], p, a, 0.95, theta_outer=[views[0]], theta_local=[views[1]])
-    binding.sparseloco_aggregate(plan, [p], [a], [views[3]])
+    binding.sparseloco_aggregate(plan, [p], [views[3]], aux=[a])
     binding.sparseloco_outer_update(plan, [views[0]], [views[3]], 1.0)
     torch.cuda.synchronize()
     got = [dict(pairs=[parity.to_np(p)], aux=[parity.to_np(a)], ef=[[parity.to_np(views[2])]],
@@ -156,8 +156,9 @@ def test_fused_update_resets_the_replicas():
         ef = [[parity._dev(x) for x in r] for r in case.ef]
         tl = [[parity._dev(x) for x in r] for r in case.theta_local]
         msgs = [plan.message_buffers() for _ in range(case.R)]
-        B.sparseloco_compress_batch(plan, th, tl, ef, [m[0] for m in msgs], [m[1] for m in msgs], 0.95)
-        B.sparseloco_aggregate_update(plan, [m[0] for m in msgs], [m[1] for m in msgs], th, 0.8, reset=tl[:2])
+        b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
+        B.sparseloco_compress_batch(plan, th, tl, ef, b_msgs, 0.95)
+        B.sparseloco_aggregate_update(plan, b_msgs, th, 0.8, reset=tl[:2])
         torch.cuda.synchronize()
         for t in range(len(case.numels)):
             new = parity.to_np(th[t])
@@ -182,6 +183,157 @@ def test_colliding_indices_many_replicas():
     for kappa in (16, 64, 128):
         parity.check(case, kappa, what="collisions kappa=%d" % kappa)
         parity.check(case, kappa, fused="no_mean", what="collisions fused kappa=%d" % kappa)
+
+
+def colliding_case(numels, R, seed, noise=1e-5):
+    """Replicas that send (almost) the same indices: shared pseudo-gradient plus a little noise of their own."""
+    rng = np.random.default_rng(seed)
+    shared = [(rng.standard_normal(n) * 1e-3).astype(np.float32) for n in numels]
+    th = [np.zeros(n, np.float32) for n in numels]
+    ef = [[np.zeros(n, np.float32) for n in numels] for _ in range(R)]
+    deltas = [[(shared[t] + (rng.standard_normal(n) * noise).astype(np.float32)).astype(np.float32)
+               for t, n in enumerate(numels)] for _ in range(R)]
+    return parity.HostCase(th, ef, delta=deltas)
+
+
+@pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("R", [9, 17, 40])
+@pytest.mark.parametrize("kappa", [200, 256])
+def test_wide_messages_many_replicas(kappa, R, quant):
+    """kappa in 129..256 (four pairs per lane in the aggregation) with several batches of eight replicas, so
+    that the prefetch of batch g + 4 and the hand-over between the four waves run; heavy collisions; separate
+    and fused line 5; a partial chunk with kappa_c < kappa."""
+    case = colliding_case([4096 * 2 + 230, 150], R, seed=kappa + R)
+    parity.check(case, kappa, quant=quant, what="wide kappa=%d R=%d" % (kappa, R))
+    parity.check(case, kappa, lr=0.8, quant=quant, fused="with_mean", what="wide fused kappa=%d R=%d" % (kappa, R))
+
+
+@pytest.mark.parametrize("R", [33, 64])
+def test_batched_compress_many_replicas(R):
+    case = gaussian_case([4096 * 2 + 77, 300], R=R, seed=600 + R, heavy=True)
+    parity.check(case, 32, batch=True, fused="no_mean", what="batched R=%d" % R)
+
+
+def test_declared_limits_of_replica_counts():
+    """SPLC_MAX_REPLICAS = 1024 replicas on a two-chunk tensor: bound as 1024 sets and 1024 messages, one batched
+    compress launch, the mean over 1024 messages, and the reset of all 1024 local parameter sets."""
+    R = B.SPLC_MAX_REPLICAS
+    n = 4096 + 500
+    rng = np.random.default_rng(1024)
+    shared = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    th = [(rng.standard_normal(n) * 0.02).astype(np.float32)]
+    ef = [[(rng.standard_normal(n) * 1e-4).astype(np.float32)] for _ in range(R)]
+    tl = [[(th[0] - (shared + (rng.standard_normal(n) * 3e-4).astype(np.float32))).astype(np.float32)] for _ in range(R)]
+    case = parity.HostCase(th, ef, theta_local=tl)
+    want = parity.run_oracle(case, 16, 0.95, 1.0)
+    plan = B.Plan(case.numels, 16)
+    g_th = [parity._dev(th[0])]
+    g_ef = [[parity._dev(e[0])] for e in ef]
+    g_tl = [[parity._dev(t[0])] for t in tl]
+    msgs = [plan.message_buffers() for _ in range(R)]
+    b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
+    b_tl = plan.bind(g_tl)
+    B.sparseloco_compress_batch(plan, g_th, b_tl, g_ef, b_msgs, 0.95)
+    dbar = [torch.full((n,), float("nan"), device="cuda")]
+    B.sparseloco_aggregate_update(plan, b_msgs, g_th, 1.0, delta_bar_out=dbar, reset=b_tl)
+    torch.cuda.synchronize()
+    got = [dict(pairs=[parity.to_np(m[0]) for m in msgs], aux=[parity.to_np(m[1]) for m in msgs],
+                ef=[[parity.to_np(e[0])] for e in g_ef], dbar=[parity.to_np(dbar[0])], theta=[parity.to_np(g_th[0])])]
+    parity.compare(got, want, "1024 replicas")
+    new = parity.to_np(g_th[0]).tobytes()
+    assert all(parity.to_np(t[0]).tobytes() == new for t in g_tl)
+    with pytest.raises(B.SparseLoCoError) as ei:            # one more than the limit is refused at bind time
+        plan.bind(g_tl + [g_tl[0]])
+    assert ei.value.status == B.SPLC_EINVAL
+    plan.close()
+
+
+def test_reset_of_64_replicas_on_ragged_tensors():
+    case = gaussian_case([4096 + 9, 100, 4096 * 2], R=64, seed=64)
+    want = parity.run_oracle(case, 32, 0.95, 1.0)
+    plan = B.Plan(case.numels, 32)
+    th = [parity._dev(x) for x in case.theta_outer]
+    ef = [[parity._dev(x) for x in r] for r in case.ef]
+    tl = [[parity._dev(x) for x in r] for r in case.theta_local]
+    msgs = [plan.message_buffers() for _ in range(case.R)]
+    b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
+    B.sparseloco_compress_batch(plan, th, tl, ef, b_msgs, 0.95)
+    B.sparseloco_aggregate_update(plan, b_msgs, th, 1.0, reset=tl)
+    torch.cuda.synchronize()
+    for t in range(len(case.numels)):
+        new = parity.to_np(th[t])
+        parity.assert_close_fp32(new, want[0]["theta"][t], "theta[%d]" % t)
+        assert all(parity.to_np(tl[r][t]).tobytes() == new.tobytes() for r in range(64))
+    plan.close()
+
+
+@pytest.mark.parametrize("variant", ["three_calls", "batched_fused"])
+@pytest.mark.parametrize("tiled", [False, True])
+def test_outer_step_replays_from_a_hip_graph(variant, tiled):
+    """The operations only enqueue kernels, so a whole outer step can be recorded into a HIP graph.  Three
+    replays, each after fresh local parameters were written by eager work and a synchronisation, each compared
+    bit for bit with the same step run eagerly on a copy of the state; the first also against the oracle."""
+    R, kappa, beta, lr = 5, 48, 0.95, 0.8
+    shapes = TILED_SHAPES if tiled else None
+    case = gaussian_case(RAGGED, R=R, seed=808, shapes=shapes)
+    want = parity.run_oracle(case, kappa, beta, lr)
+    plan = B.Plan(case.shapes if tiled else case.numels, kappa, True, tiled=tiled)
+
+    class State:
+        def __init__(self):
+            self.th = [parity._dev(x) for x in case.theta_outer]
+            self.ef = [[parity._dev(x) for x in r] for r in case.ef]
+            self.tl = [[parity._dev(x) for x in r] for r in case.theta_local]
+            self.msgs = [plan.message_buffers() for _ in range(R)]
+            self.dbar = [torch.zeros(n, device="cuda") for n in case.numels]
+            self.b_th, self.b_ef, self.b_tl, self.b_dbar = (plan.bind(x) for x in (self.th, self.ef, self.tl, self.dbar))
+            self.b_msgs = plan.bind_messages([m[0] for m in self.msgs], [m[1] for m in self.msgs])
+
+        def step(self):
+            if variant == "three_calls":
+                for r in range(R):
+                    B.sparseloco_compress(plan, self.b_ef, self.msgs[r][0], self.msgs[r][1], beta, theta_outer=self.b_th,
+                                          theta_local=self.b_tl, replica=r)
+                B.sparseloco_aggregate(plan, self.b_msgs, self.b_dbar)
+                B.sparseloco_outer_update(plan, self.b_th, self.b_dbar, lr)
+            else:
+                B.sparseloco_compress_batch(plan, self.b_th, self.b_tl, self.b_ef, self.b_msgs, beta)
+                B.sparseloco_aggregate_update(plan, self.b_msgs, self.b_th, lr, delta_bar_out=self.b_dbar)
+
+        def tensors(self):
+            return self.th + [x for r in self.ef for x in r] + [x for m in self.msgs for x in m] + self.dbar
+
+    warm, a, b = State(), State(), State()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        warm.step()                                                  # loads the kernels outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        a.step()
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for rep in range(3):
+        if rep > 0:                                                  # the replicas' next inner phase, eagerly
+            for r in range(R):
+                for t, n in enumerate(case.numels):
+                    fresh = a.th[t] - torch.randn(n, generator=gen, device="cuda") * 1e-3
+                    a.tl[r][t].copy_(fresh)
+                    b.tl[r][t].copy_(fresh)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        b.step()
+        torch.cuda.synchronize()
+        for x, y in zip(a.tensors(), b.tensors()):
+            assert torch.equal(x, y), "replay %d differs from the eager step" % rep
+        if rep == 0:
+            got = [dict(pairs=[parity.to_np(m[0]) for m in a.msgs], aux=[parity.to_np(m[1]) for m in a.msgs],
+                        ef=[[parity.to_np(x) for x in r] for r in a.ef], dbar=[parity.to_np(x) for x in a.dbar],
+                        theta=[parity.to_np(x) for x in a.th])]
+            parity.compare(got, want, "graph replay 0")
+    plan.close()
 
 
 def test_workload0_full():
@@ -227,9 +379,13 @@ def test_error_returns_do_not_launch():
     plan = B.Plan([4096, 10], 32)
     e = [torch.zeros(4096, device="cuda"), torch.zeros(10, device="cuda")]
     p, a = plan.message_buffers()
-    with pytest.raises(B.SparseLoCoError) as ei:
+    with pytest.raises(ValueError):                     # the binding refuses a missing tensor on the host
         B.sparseloco_compress(plan, e, p, a, 0.95, theta_outer=e, theta_local=[e[0], None])
-    assert ei.value.status == B.SPLC_EINVAL
+    L = B.lib()
+    import ctypes
+    h = ctypes.c_void_p()
+    ptrs = (ctypes.c_void_p * 2)(e[0].data_ptr(), None)
+    assert L.sparseloco_tensors_bind(ctypes.byref(h), plan.handle, 1, ptrs, B.SPLC_F32, None) == B.SPLC_EINVAL
     big = torch.zeros(2 * (4096 + 8), device="cuda", dtype=torch.bfloat16)
     with pytest.raises(B.SparseLoCoError) as ei:        # a bf16 source that starts at an odd element: 2-byte aligned
         B.sparseloco_compress(plan, e, p, a, 0.95, delta=[big[1:4097], big[4100:4110]])
@@ -238,8 +394,16 @@ def test_error_returns_do_not_launch():
         B.sparseloco_compress(plan, e, p, a, float("inf"), delta=e)
     assert ei.value.status == B.SPLC_EINVAL
     with pytest.raises(B.SparseLoCoError) as ei:
-        B.sparseloco_aggregate(plan, [], [], e)
+        B.sparseloco_aggregate(plan, [], e, aux=[])
     assert ei.value.status == B.SPLC_EINVAL
+    with pytest.raises(B.SparseLoCoError) as ei:        # replica index beyond the sets of a multi-set binding
+        B.sparseloco_compress(plan, plan.bind([e, e]), p, a, 0.95, delta=e, replica=2)
+    assert ei.value.status == B.SPLC_EINVAL
+    other = B.Plan([4096], 32)
+    with pytest.raises(B.SparseLoCoError) as ei:        # a binding made for another plan
+        B.sparseloco_outer_update(plan, other.bind([e[0]]), e, 1.0)
+    assert ei.value.status == B.SPLC_EPLAN
+    other.close()
     plan.close()
 
 
@@ -288,7 +452,7 @@ def test_aggregate_survives_malformed_messages():
     guard = 7.0
     bufs = [torch.full((n + 64,), guard, device="cuda") for n in numels]
     dbar = [b[:n] for b, n in zip(bufs, numels)]
-    B.sparseloco_aggregate(plan, pairs, scales, dbar)
+    B.sparseloco_aggregate(plan, pairs, dbar, aux=scales)
     torch.cuda.synchronize()
     for b, n in zip(bufs, numels):
         assert bool(torch.isfinite(b[:n]).all()) and bool((b[n:] == guard).all())
