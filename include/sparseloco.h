@@ -146,11 +146,14 @@ int sparseloco_plan_set_radix_counter(sparseloco_plan* plan, uint32_t* device_co
 /*
  * The chunk table a plan with these tensors holds, computed on the host (no GPU needed): for checking tools.
  * layout: SPLC_LAYOUT_*; rows may be NULL for the flat layout (then cols[i] = numel).  Writes up to `capacity`
- * entries of 32 bytes each to `out` (may be NULL), in the order the kernels walk them:
- *   uint32 tensor; uint32 n_c; uint64 offset; uint32 stride; uint8 h, w, last_w, vec; uint32 id; uint32 reserved
+ * entries of 32 bytes each to `out` (may be NULL):
+ *   uint32 tensor; uint32 n_c; uint64 offset; uint32 stride; uint8 h, w, last_w, vec; uint32 id; uint32 strip
  * -- local index idx of chunk `id` (present iff idx/64 < h-1 and idx%64 < w, or idx/64 == h-1 and idx%64 < last_w)
- * is element offset + (idx / 64) * stride + idx % 64 of tensor `tensor`.  Returns the number of chunks, or a
- * negative status.
+ * is element offset + (idx / 64) * stride + idx % 64 of tensor `tensor`.  vec: bit 0 = the chunk is complete and
+ * is read with 4-element vector accesses as fp32, bit 1 = also as bf16.  strip: 0, or 1 + j for the j-th of four
+ * complete tiles side by side that a tiled plan hands to one workgroup (which then reads whole 256-element rows
+ * from the first tile's origin).  Order: first the chunks that workgroups take one by one, in launch order, then
+ * the strips' members.  Returns the number of chunks, or a negative status.
  */
 int64_t sparseloco_chunk_table(int n_tensors, const int64_t* rows, const int64_t* cols, int layout,
                                void* out, int64_t capacity);

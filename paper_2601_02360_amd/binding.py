@@ -133,7 +133,7 @@ def chunk_table(shapes: Sequence, tiled: bool):
     if total < 0:
         raise SparseLoCoError(int(total), "sparseloco_chunk_table")
     dt = np.dtype([("tensor", "<u4"), ("n_c", "<u4"), ("offset", "<u8"), ("stride", "<u4"), ("h", "u1"), ("w", "u1"),
-                   ("last_w", "u1"), ("vec", "u1"), ("id", "<u4"), ("reserved", "<u4")])
+                   ("last_w", "u1"), ("vec", "u1"), ("id", "<u4"), ("strip", "<u4")])
     assert dt.itemsize == 32
     out = np.zeros(int(total), dt)
     got = lib().sparseloco_chunk_table(n, rows, cols, layout, out.ctypes.data_as(ctypes.c_void_p), int(total))

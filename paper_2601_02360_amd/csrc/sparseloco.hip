@@ -221,6 +221,10 @@ __device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, ui
     uint64_t prefix = 0;
     uint32_t need = kappa_c;
     int hi_bit = 43;
+    // The filter path may already have published counts for this chunk (when another group of the workgroup
+    // forced the general path): start from zero.  The first barrier of the loop below orders this.
+    if (tid < 16) sh.bucket[tid] = 0;
+    if (tid < 4) sh.wmax[tid] = 0;
 #pragma unroll 1
     for (int pass = 0; pass < 6; ++pass) {
         const int width = pass < 5 ? 8 : 3;
@@ -294,7 +298,11 @@ template <int QUANT>
 __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x)[16], int tid, int lane, int wave,
                                                      uint32_t n_c, uint32_t pmask, uint32_t kappa, int force_radix,
                                                      uint32_t* radix_counter, uint16_t* __restrict__ pairs_c,
-                                                     float* __restrict__ values_c, float* __restrict__ scales_c) {
+                                                     float* __restrict__ values_c, float* __restrict__ scales_c,
+                                                     uint32_t* group_ok = nullptr, int group = 0) {
+    // group_ok: four flags in LDS when four 256-lane groups of one workgroup each select a chunk of their own
+    // side by side (tid, lane, wave are then group-local and `sh` is the group's own).  Workgroup barriers must
+    // be reached by all groups alike, so the groups agree on the path: if one needs the radix select, all take it.
     const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
     sh.cand[tid] = 0;
     if (tid < 2) sh.cand[kCandCap + tid] = 0;
@@ -372,7 +380,13 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
             selected_by_filter = true;
         }
     }
-    __syncthreads();
+    if (group_ok) {
+        if (tid == 0) group_ok[group] = selected_by_filter ? 1u : 0u;
+        __syncthreads();
+        selected_by_filter = (group_ok[0] & group_ok[1] & group_ok[2] & group_ok[3]) != 0;
+    } else {
+        __syncthreads();
+    }
     if (!selected_by_filter) {
         radix_select(sh, x, tid, pmask, kappa_c);
         if (radix_counter && tid == 0) atomicAdd(radix_counter, 1u);      // diagnostic: chunks on the general path
@@ -513,6 +527,131 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const ChunkDesc* __r
     else
         compress_body<MODE, QUANT, false>(sh, chunks, src_a, src_b, ef_tab, beta, kappa, force_radix, radix_counter,
                                           pairs_out, aux_out);
+}
+
+// ---- 64 x 64 tiles, four at a time ("strip"): rows of a strip are 1024 contiguous bytes ----
+//
+// A workgroup that owns one 64 x 64 tile touches 256-byte row segments; when the matrix's row length is not a
+// multiple of 32 floats every such segment straddles three 128-byte cache lines instead of two, and the lines on
+// a tile's left and right edge are requested again by its neighbours.  So wherever four complete tiles lie side
+// by side, ONE workgroup of 1024 lanes takes all four: global memory is accessed row by row (a wave covers one
+// 1024-byte row of the strip per instruction: nine lines instead of twelve, none shared with another
+// workgroup), the folded values pass through LDS, where each 256-lane group picks up "its" tile in the usual
+// chunk layout and runs the selection exactly as the one-tile kernel does, and the new error-feedback values go
+// back the same way.  Tiles left over at the end of a tile row, edge tiles and 1-D tensors stay with the
+// one-tile kernels.
+constexpr int kStripTiles = 4;
+constexpr int kStripThreads = kStripTiles * kThreads;
+// Two strip workgroups per compute unit (8 waves per SIMD, 64 registers per lane, 2 x 77 KB of LDS): one of
+// them selects while the other one's rows are in flight.
+
+struct StripShared {
+    float tile[kStripTiles][kChunk];     // local index order: [row * 64 + column]
+    SelectShared sel[kStripTiles];
+    uint32_t group_ok[kStripTiles];
+};
+
+// Row-wise position of lane `lane` of wave `wave` (0..15) in round i (0..3): local row 16 i + wave of the strip,
+// floats 4 lane .. 4 lane + 3 of that row, i.e. tile lane / 16, local columns 4 (lane % 16) ...
+__device__ __forceinline__ uint32_t strip_row(int i, int wave) { return 16u * (uint32_t)i + (uint32_t)wave; }
+
+template <int MODE, int QUANT>
+__global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const ChunkDesc* __restrict__ strips,
+                                                                       const void* const* __restrict__ src_a,
+                                                                       const void* const* __restrict__ src_b,
+                                                                       float* const* __restrict__ ef_tab, float beta,
+                                                                       uint32_t kappa, int force_radix,
+                                                                       uint32_t* radix_counter,
+                                                                       uint16_t* __restrict__ pairs_out,
+                                                                       float* __restrict__ aux_out) {
+    __shared__ __align__(16) StripShared sm;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // 0..15
+    const ChunkDesc d = strips[blockIdx.x];
+    float* const pe = ef_tab[d.tensor] + d.offset;
+    const uint32_t q = (uint32_t)lane >> 4, lc = ((uint32_t)lane & 15u) * 4u;
+
+    // ---- rows in: fold in registers, e' to LDS ----
+    {
+        float4 ev[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ev[i] = stream_load4(pe + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+        float x[16];
+        if (MODE == MODE_PARAMS_F32) {
+            const float* po = static_cast<const float*>(src_a[d.tensor]) + d.offset;
+            const float* pl = static_cast<const float*>(src_b[d.tensor]) + d.offset;
+            float4 ov[4], lv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ov[i] = stream_load4(po + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) lv[i] = stream_load4(pl + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[4 * i + 0] = fold(beta, ev[i].x, __fsub_rn(ov[i].x, lv[i].x));
+                x[4 * i + 1] = fold(beta, ev[i].y, __fsub_rn(ov[i].y, lv[i].y));
+                x[4 * i + 2] = fold(beta, ev[i].z, __fsub_rn(ov[i].z, lv[i].z));
+                x[4 * i + 3] = fold(beta, ev[i].w, __fsub_rn(ov[i].w, lv[i].w));
+            }
+        } else if (MODE == MODE_DIRECT_F32) {
+            const float* pd = static_cast<const float*>(src_a[d.tensor]) + d.offset;
+            float4 dv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dv[i] = stream_load4(pd + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[4 * i + 0] = fold(beta, ev[i].x, dv[i].x);
+                x[4 * i + 1] = fold(beta, ev[i].y, dv[i].y);
+                x[4 * i + 2] = fold(beta, ev[i].z, dv[i].z);
+                x[4 * i + 3] = fold(beta, ev[i].w, dv[i].w);
+            }
+        } else {
+            const uint16_t* pd = static_cast<const uint16_t*>(src_a[d.tensor]) + d.offset;
+            uint2 dv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dv[i] = stream_load4(pd + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[4 * i + 0] = fold(beta, ev[i].x, __uint_as_float(dv[i].x << 16));
+                x[4 * i + 1] = fold(beta, ev[i].y, __uint_as_float(dv[i].x & 0xFFFF0000u));
+                x[4 * i + 2] = fold(beta, ev[i].z, __uint_as_float(dv[i].y << 16));
+                x[4 * i + 3] = fold(beta, ev[i].w, __uint_as_float(dv[i].y & 0xFFFF0000u));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<float4*>(&sm.tile[q][strip_row(i, wave) * 64u + lc]) =
+                make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+    }
+    __syncthreads();
+
+    // ---- each 256-lane group selects in its own tile ----
+    {
+        const int group = __builtin_amdgcn_readfirstlane(tid >> 8);
+        const int gtid = tid & (kThreads - 1);
+        const int gwave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
+        const uint64_t c = (uint64_t)d.id + (uint64_t)group;
+        float x[16];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(&sm.tile[group][s * 1024 + gtid * 4]);
+            x[4 * s] = v.x; x[4 * s + 1] = v.y; x[4 * s + 2] = v.z; x[4 * s + 3] = v.w;
+        }
+        select_quantise_pack<QUANT>(sm.sel[group], x, gtid, lane, gwave, (uint32_t)kChunk, 0xFFFFu, kappa, force_radix,
+                                    radix_counter, pairs_out + c * kappa, aux_out + c * kappa, aux_out + 2 * c,
+                                    sm.group_ok, group);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            *reinterpret_cast<float4*>(&sm.tile[group][s * 1024 + gtid * 4]) =
+                make_float4(x[4 * s], x[4 * s + 1], x[4 * s + 2], x[4 * s + 3]);
+    }
+    __syncthreads();
+
+    // ---- rows out ----
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        stream_store4(pe + (size_t)strip_row(i, wave) * d.stride + 4 * lane,
+                      *reinterpret_cast<const float4*>(&sm.tile[q][strip_row(i, wave) * 64u + lc]));
 }
 
 // Lines 1-4 for R replicas that share theta_outer (several replicas simulated on one GPU): the
@@ -821,6 +960,71 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const ChunkDesc* __
                                              eta, n_reset, n_tensors, reset_tab);
 }
 
+// Line 5 for a strip of four complete 64 x 64 tiles (see compress_strip_kernel): the four 256-lane groups
+// accumulate the messages of their tiles side by side; the mean (and the parameters) leave and enter row by row.
+template <int QUANT, int UPDATE>
+__global__ __launch_bounds__(kStripThreads, 8) void aggregate_strip_kernel(const ChunkDesc* __restrict__ strips,
+                                                                        int n_replicas, uint32_t kappa,
+                                                                        const uint16_t* const* __restrict__ pairs_tab,
+                                                                        const float* const* __restrict__ aux_tab,
+                                                                        float* const* __restrict__ dbar_tab,
+                                                                        float* const* __restrict__ theta_tab, float eta,
+                                                                        int n_reset, uint32_t n_tensors,
+                                                                        float* const* __restrict__ reset_tab) {
+    __shared__ __align__(16) float acc[kStripTiles][kChunk];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int group = __builtin_amdgcn_readfirstlane(tid >> 8);
+    const int gtid = tid & (kThreads - 1);
+    const int gwave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
+    const ChunkDesc d = strips[blockIdx.x];
+    const uint32_t q = (uint32_t)lane >> 4, lc = ((uint32_t)lane & 15u) * 4u;
+    float* th = UPDATE ? theta_tab[d.tensor] + d.offset : nullptr;
+    float* po = dbar_tab ? dbar_tab[d.tensor] + d.offset : nullptr;
+    float4* acc4 = reinterpret_cast<float4*>(&acc[group][0]);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) acc4[s * kThreads + gtid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const uint32_t kappa_c = kappa < (uint32_t)kChunk ? kappa : (uint32_t)kChunk;
+    const uint64_t c = (uint64_t)d.id + (uint64_t)group;
+    if (kappa_c <= 64) {
+        accumulate_chunk<QUANT, 1>(acc[group], c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane, gwave);
+    } else if (kappa_c <= 128) {
+        accumulate_chunk<QUANT, 2>(acc[group], c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane, gwave);
+    } else if (kappa_c <= 256) {
+        accumulate_chunk<QUANT, 4>(acc[group], c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane, gwave);
+    } else {
+        __syncthreads();
+        if (gwave == 0) accumulate_chunk_any<QUANT>(acc[group], c, kappa, kappa_c, n_replicas, pairs_tab, aux_tab, lane);
+        __syncthreads();
+    }
+    const float m = (float)n_replicas;
+    // The parameters are fetched only now: held across the accumulation they would cost the registers that let
+    // two of these workgroups share a compute unit, and the second workgroup hides this latency.
+    float4 tv[4];
+    if (UPDATE) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tv[i] = stream_load4(th + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const size_t at = (size_t)strip_row(i, wave) * d.stride + 4 * lane;
+        float4 v = *reinterpret_cast<const float4*>(&acc[q][strip_row(i, wave) * 64u + lc]);
+        v.x = __fdiv_rn(v.x, m); v.y = __fdiv_rn(v.y, m); v.z = __fdiv_rn(v.z, m); v.w = __fdiv_rn(v.w, m);
+        if (po) stream_store4(po + at, v);
+        if (UPDATE) {
+            float4 t = tv[i];
+            t.x = __fsub_rn(t.x, __fmul_rn(eta, v.x));
+            t.y = __fsub_rn(t.y, __fmul_rn(eta, v.y));
+            t.z = __fsub_rn(t.z, __fmul_rn(eta, v.z));
+            t.w = __fsub_rn(t.w, __fmul_rn(eta, v.w));
+            stream_store4(th + at, t);
+            for (int r = 0; r < n_reset; ++r)
+                stream_store4(reset_tab[(size_t)r * n_tensors + d.tensor] + d.offset + at, t);
+        }
+    }
+}
+
 // Line 5, second half: theta = fl(theta - fl(eta * delta_bar)).
 template <bool VEC>
 __device__ __forceinline__ void outer_update_body(const ChunkDesc* __restrict__ chunks,
@@ -879,10 +1083,21 @@ struct sparseloco_plan {
     // Chunk table, ordered [edge chunks | complete, vector-able for fp32 only | complete, vector-able for
     // fp32 and bf16]; every entry carries its chunk number.  The slow element-wise chunks come first so
     // that they overlap with the streaming ones instead of forming the tail of the launch.
+    // A tiled plan takes complete tiles four at a time where four lie side by side ("strips", one entry each:
+    // origin, stride and chunk number of the first tile); only the other chunks are in the table above.  Its
+    // outer update, which is element-wise, walks the tensors as flat chunks (a table of its own).
+    // One device allocation holds [chunks | strips | flat chunks of the update | every chunk one by one].
     ChunkDesc* d_chunks = nullptr;
     ChunkDesc* h_chunks = nullptr;       // pinned source of the asynchronous upload, kept until destroy
+    int64_t n_entries = 0;               // entries of the chunk table (= n_chunks unless there are strips)
     int64_t n_gen_f32 = 0;               // entries of the first class
     int64_t n_gen_bf16 = 0;              // entries of the first two classes
+    int64_t n_strips = 0;
+    ChunkDesc* d_strips = nullptr;       // inside d_chunks' allocation
+    ChunkDesc* d_update = nullptr;       // = d_chunks for a flat plan
+    int64_t n_update = 0, n_update_gen = 0;
+    ChunkDesc* d_all = nullptr;          // every chunk one by one, for the batched compress (= d_chunks without strips)
+    int64_t n_all_gen = 0;
 };
 
 // n_sets lists of n_tensors device pointers, set-major, resident on the device.
@@ -951,18 +1166,25 @@ unsigned gen_entries(const sparseloco_plan* plan, bool bf16_source) {
 template <int MODE, int QUANT>
 void launch_compress(const sparseloco_plan* plan, const void* const* a, const void* const* b, float* const* ef,
                      float beta, uint16_t* pairs_out, float* aux_out, hipStream_t stream) {
-    hipLaunchKernelGGL((compress_kernel<MODE, QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
-                       plan->d_chunks, gen_entries(plan, MODE == MODE_DIRECT_BF16), a, b, ef, beta,
-                       (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, plan->radix_counter, pairs_out,
-                       aux_out);
+    const int force_radix = plan->select == SPLC_SELECT_RADIX ? 1 : 0;
+    if (plan->n_strips > 0)
+        hipLaunchKernelGGL((compress_strip_kernel<MODE, QUANT>), dim3((unsigned)plan->n_strips), dim3(kStripThreads), 0,
+                           stream, plan->d_strips, a, b, ef, beta, (uint32_t)plan->kappa, force_radix,
+                           plan->radix_counter, pairs_out, aux_out);
+    if (plan->n_entries > 0)
+        hipLaunchKernelGGL((compress_kernel<MODE, QUANT>), dim3((unsigned)plan->n_entries), dim3(kThreads), 0, stream,
+                           plan->d_chunks, gen_entries(plan, MODE == MODE_DIRECT_BF16), a, b, ef, beta,
+                           (uint32_t)plan->kappa, force_radix, plan->radix_counter, pairs_out, aux_out);
 }
 
 template <int QUANT>
 void launch_compress_batch(const sparseloco_plan* plan, int n_replicas, const float* const* to,
                            const float* const* tl, float* const* ef, float beta, uint16_t* const* pairs,
                            float* const* aux, hipStream_t stream) {
+    // Strips are taken tile by tile here: a strip entry is followed, in the device table, by nothing this kernel
+    // could use, so the batched path walks the per-chunk view kept behind the update table.
     hipLaunchKernelGGL((compress_batch_kernel<QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
-                       plan->d_chunks, gen_entries(plan, false), n_replicas, (uint32_t)plan->n_tensors, to, tl, ef,
+                       plan->d_all, (unsigned)plan->n_all_gen, n_replicas, (uint32_t)plan->n_tensors, to, tl, ef,
                        beta, (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, plan->radix_counter, pairs,
                        aux);
 }
@@ -971,9 +1193,14 @@ template <int QUANT, int UPDATE>
 void launch_aggregate(const sparseloco_plan* plan, int n_replicas, const uint16_t* const* pairs,
                       const float* const* aux, float* const* dbar, float* const* theta, float eta, int n_reset,
                       float* const* reset, hipStream_t stream) {
-    hipLaunchKernelGGL((aggregate_kernel<QUANT, UPDATE>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
-                       plan->d_chunks, gen_entries(plan, false), n_replicas, (uint32_t)plan->kappa, pairs, aux, dbar,
-                       theta, eta, n_reset, (uint32_t)plan->n_tensors, reset);
+    if (plan->n_strips > 0)
+        hipLaunchKernelGGL((aggregate_strip_kernel<QUANT, UPDATE>), dim3((unsigned)plan->n_strips), dim3(kStripThreads),
+                           0, stream, plan->d_strips, n_replicas, (uint32_t)plan->kappa, pairs, aux, dbar, theta, eta,
+                           n_reset, (uint32_t)plan->n_tensors, reset);
+    if (plan->n_entries > 0)
+        hipLaunchKernelGGL((aggregate_kernel<QUANT, UPDATE>), dim3((unsigned)plan->n_entries), dim3(kThreads), 0, stream,
+                           plan->d_chunks, gen_entries(plan, false), n_replicas, (uint32_t)plan->kappa, pairs, aux,
+                           dbar, theta, eta, n_reset, (uint32_t)plan->n_tensors, reset);
 }
 
 // Shared by sparseloco_aggregate and sparseloco_aggregate_update.
@@ -1051,9 +1278,41 @@ void append_chunks(std::vector<ChunkDesc>& table, uint32_t tensor, int64_t rows,
     }
 }
 
-// Validates the tensor list and counts its chunks; fills the table if one is given.
-int build_chunk_table(int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled, int64_t* n_chunks_out,
-                      int64_t* n_params_out, std::vector<ChunkDesc>* table) {
+int chunk_class(const ChunkDesc& d) { return d.vec == 0 ? 0 : (d.vec == 1 ? 1 : 2); }
+
+// Order in which workgroups take the entries: element-wise chunks first (they are the slow ones and should
+// overlap with the rest instead of forming the tail), then the chunks that allow vector accesses for fp32 only,
+// then those that allow them for bf16 too.  For a tiled plan, inside each class every XCD gets a run of
+// consecutive tiles: workgroups go to the eight XCDs round-robin by number, neighbouring tiles of a tile row
+// continue each other's row segments (and share the cache lines on their common edge when the row length is no
+// multiple of 32 floats), so neighbours should meet in one L2.  Only the order of processing changes: a chunk's
+// number, and with it the place of its pairs in the message, is its `id`.
+void order_for_launch(std::vector<ChunkDesc>& table, bool deal_to_xcds) {
+    std::stable_sort(table.begin(), table.end(),
+                     [](const ChunkDesc& a, const ChunkDesc& b) { return chunk_class(a) < chunk_class(b); });
+    if (!deal_to_xcds) return;
+    size_t start = 0;
+    while (start < table.size()) {
+        size_t end = start;
+        while (end < table.size() && chunk_class(table[end]) == chunk_class(table[start])) ++end;
+        const std::vector<ChunkDesc> seg(table.begin() + (ptrdiff_t)start, table.begin() + (ptrdiff_t)end);
+        size_t next = 0;
+        for (size_t r = 0; r < 8; ++r)
+            for (size_t pos = start + (r + 8 - start % 8) % 8; pos < end; pos += 8) table[pos] = seg[next++];
+        start = end;
+    }
+}
+
+struct ChunkTables {
+    int64_t n_chunks = 0, n_params = 0;
+    std::vector<ChunkDesc> all;          // every chunk, launch order
+    std::vector<ChunkDesc> rest;         // tiled plans: the chunks outside strips, launch order
+    std::vector<ChunkDesc> strips;       // tiled plans: one entry per strip (its first tile), launch order
+    std::vector<ChunkDesc> update;       // tiled plans: flat chunks for the element-wise update
+};
+
+// Validates the tensor list and counts its chunks; fills the tables if asked to.
+int build_chunk_tables(int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled, ChunkTables& t, bool fill) {
     if (n_tensors < 1 || !cols || (tiled && !rows)) return SPLC_EINVAL;
     int64_t n_chunks = 0, n_params = 0;
     for (int i = 0; i < n_tensors; ++i) {
@@ -1069,35 +1328,56 @@ int build_chunk_table(int n_tensors, const int64_t* rows, const int64_t* cols, b
         n_params += r * c;
     }
     if (n_chunks > 0x7FFFFFFF) return SPLC_EINVAL;      // one workgroup per chunk in a 1-D grid
-    *n_chunks_out = n_chunks;
-    *n_params_out = n_params;
-    if (!table) return SPLC_OK;
-    table->clear();
-    table->reserve((size_t)n_chunks);
-    for (int i = 0; i < n_tensors; ++i)
-        append_chunks(*table, (uint32_t)i, tiled ? rows[i] : 1, cols[i], tiled);
-    for (size_t k = 0; k < table->size(); ++k) (*table)[k].id = (uint32_t)k;
-    auto cls = [](const ChunkDesc& d) { return d.vec == 0 ? 0 : (d.vec == 1 ? 1 : 2); };
-    std::stable_sort(table->begin(), table->end(),
-                     [&](const ChunkDesc& a, const ChunkDesc& b) { return cls(a) < cls(b); });
+    t.n_chunks = n_chunks;
+    t.n_params = n_params;
+    if (!fill) return SPLC_OK;
+    t.all.clear();
+    t.all.reserve((size_t)n_chunks);
+    for (int i = 0; i < n_tensors; ++i) append_chunks(t.all, (uint32_t)i, tiled ? rows[i] : 1, cols[i], tiled);
+    for (size_t k = 0; k < t.all.size(); ++k) t.all[k].id = (uint32_t)k;
+    t.rest.clear();
+    t.strips.clear();
+    t.update.clear();
     if (tiled) {
-        // Workgroups go to the eight XCDs round-robin by number.  Neighbouring tiles of a tile row continue each
-        // other's 256-byte row segments (and share the cache lines on their common edge when the row length is
-        // no multiple of 32 floats), so each XCD is given a run of consecutive tiles (inside each class of the
-        // table) instead of every eighth one.  Only the order of processing changes: a chunk's number, and with
-        // it the place of its pairs in the message, is its `id`.
-        size_t start = 0;
-        while (start < table->size()) {
-            size_t end = start;
-            while (end < table->size() && cls((*table)[end]) == cls((*table)[start])) ++end;
-            const std::vector<ChunkDesc> seg(table->begin() + (ptrdiff_t)start, table->begin() + (ptrdiff_t)end);
-            size_t next = 0;
-            for (size_t r = 0; r < 8; ++r)
-                for (size_t pos = start + (r + 8 - start % 8) % 8; pos < end; pos += 8) (*table)[pos] = seg[next++];
-            start = end;
+        // Strips: four complete tiles side by side, in matrices whose row length is no multiple of 32 floats (with
+        // such a multiple a tile's 256-byte row segments are two whole cache lines already, and the one-tile
+        // kernel, which needs no trip through LDS, is the faster one: measured 6.0 against 5.8 TB/s) but even (so
+        // that rows of a bf16 source start on dword boundaries too).  Tiles of one tile row have consecutive numbers.
+        size_t k = 0;
+        for (int i = 0; i < n_tensors; ++i) {
+            const int64_t r = rows[i], c = cols[i];
+            if (r * c == 0) continue;
+            if (r == 1) { k += (size_t)((c + kChunk - 1) / kChunk); continue; }
+            const int64_t nbi = (r + 63) / 64, nbj = (c + 63) / 64, full_cols = c / 64;
+            for (int64_t bi = 0; bi < nbi; ++bi, k += (size_t)nbj) {
+                if (c % 32 == 0 || c % 2 != 0 || (bi + 1) * 64 > r) continue;
+                for (int64_t s4 = 0; s4 + kStripTiles <= full_cols; s4 += kStripTiles)
+                    for (int j = 0; j < kStripTiles; ++j) t.all[k + (size_t)(s4 + j)].reserved = 1u + (uint32_t)j;
+            }
         }
+        for (const ChunkDesc& cd : t.all) {
+            if (cd.reserved == 0) t.rest.push_back(cd);
+            else if (cd.reserved == 1) t.strips.push_back(cd);
+        }
+        order_for_launch(t.rest, true);
+        // Strips of one tile row continue each other's rows: every XCD gets a run of consecutive strips.
+        {
+            const std::vector<ChunkDesc> seg(t.strips);
+            size_t next = 0;
+            for (size_t x = 0; x < 8; ++x)
+                for (size_t pos = x; pos < seg.size(); pos += 8) t.strips[pos] = seg[next++];
+        }
+        for (int i = 0; i < n_tensors; ++i) append_chunks(t.update, (uint32_t)i, 1, rows[i] * cols[i], false);
+        order_for_launch(t.update, false);
     }
+    order_for_launch(t.all, tiled);
     return SPLC_OK;
+}
+
+int64_t count_class0(const std::vector<ChunkDesc>& v) {
+    int64_t n = 0;
+    for (const ChunkDesc& cd : v) n += cd.vec == 0;
+    return n;
 }
 
 int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const int64_t* cols, bool tiled, int chunk,
@@ -1106,9 +1386,8 @@ int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const 
     *out = nullptr;
     if (chunk != kChunk || kappa < 1 || kappa > kChunk) return SPLC_EINVAL;
     if (quant_mode != SPLC_QUANT_NONE && quant_mode != SPLC_QUANT_2BIT) return SPLC_EINVAL;
-    int64_t n_chunks = 0, n_params = 0;
-    std::vector<ChunkDesc> table;
-    int rc = build_chunk_table(n_tensors, tiled ? rows : nullptr, cols, tiled, &n_chunks, &n_params, &table);
+    ChunkTables t;
+    int rc = build_chunk_tables(n_tensors, tiled ? rows : nullptr, cols, tiled, t, true);
     if (rc != SPLC_OK) return rc;
     sparseloco_plan* plan = new (std::nothrow) sparseloco_plan();
     if (!plan) return SPLC_ENOMEM;
@@ -1117,21 +1396,37 @@ int plan_build(sparseloco_plan** out, int n_tensors, const int64_t* rows, const 
     plan->kappa = kappa;
     plan->quant = quant_mode;
     plan->layout = tiled ? SPLC_LAYOUT_TILE64 : SPLC_LAYOUT_FLAT;
-    plan->n_chunks = n_chunks;
-    plan->n_params = n_params;
+    plan->n_chunks = t.n_chunks;
+    plan->n_params = t.n_params;
     plan->numel.resize((size_t)n_tensors);
     for (int i = 0; i < n_tensors; ++i) plan->numel[(size_t)i] = (tiled ? rows[i] : 1) * cols[i];
-    for (const ChunkDesc& cd : table) {
+    const bool with_strips = !t.strips.empty();
+    const std::vector<ChunkDesc>& main_table = with_strips ? t.rest : t.all;
+    plan->n_entries = (int64_t)main_table.size();
+    for (const ChunkDesc& cd : main_table) {
         plan->n_gen_f32 += cd.vec == 0;
         plan->n_gen_bf16 += cd.vec != 3;
     }
-    if (n_chunks > 0) {
-        const size_t bytes = (size_t)n_chunks * sizeof(ChunkDesc);
+    plan->n_strips = (int64_t)t.strips.size();
+    plan->n_update = tiled ? (int64_t)t.update.size() : plan->n_entries;
+    plan->n_update_gen = tiled ? count_class0(t.update) : plan->n_gen_f32;
+    plan->n_all_gen = count_class0(t.all);
+    // device layout: [main table | strips | update table (tiled) | every chunk (with strips)]
+    const size_t n_main = main_table.size(), n_str = t.strips.size(), n_upd = tiled ? t.update.size() : 0,
+                 n_all = with_strips ? t.all.size() : 0, total = n_main + n_str + n_upd + n_all;
+    if (total > 0) {
+        const size_t bytes = total * sizeof(ChunkDesc);
         if (hipHostMalloc(reinterpret_cast<void**>(&plan->h_chunks), bytes, hipHostMallocDefault) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&plan->d_chunks), bytes) != hipSuccess) {
             rc = SPLC_ENOMEM;
         } else {
-            std::copy(table.begin(), table.end(), plan->h_chunks);
+            std::copy(main_table.begin(), main_table.end(), plan->h_chunks);
+            std::copy(t.strips.begin(), t.strips.end(), plan->h_chunks + n_main);
+            if (tiled) std::copy(t.update.begin(), t.update.end(), plan->h_chunks + n_main + n_str);
+            if (with_strips) std::copy(t.all.begin(), t.all.end(), plan->h_chunks + n_main + n_str + n_upd);
+            plan->d_strips = plan->d_chunks + n_main;
+            plan->d_update = tiled ? plan->d_chunks + n_main + n_str : plan->d_chunks;
+            plan->d_all = with_strips ? plan->d_chunks + n_main + n_str + n_upd : plan->d_chunks;
             if (hipMemcpyAsync(plan->d_chunks, plan->h_chunks, bytes, hipMemcpyHostToDevice,
                                static_cast<hipStream_t>(stream)) != hipSuccess)
                 rc = SPLC_EHIP;
@@ -1161,7 +1456,7 @@ int sparseloco_plan_create_2d(sparseloco_plan** out, int n_tensors, const int64_
 
 void sparseloco_plan_destroy(sparseloco_plan* plan) {
     if (!plan) return;
-    if (plan->d_chunks) (void)hipFree(plan->d_chunks);              // waits for the device
+    if (plan->d_chunks) (void)hipFree(plan->d_chunks);              // waits for the device; holds all tables
     if (plan->h_chunks) (void)hipHostFree(plan->h_chunks);
     delete plan;
 }
@@ -1190,8 +1485,6 @@ int64_t sparseloco_chunk_table(int n_tensors, const int64_t* rows, const int64_t
     if (layout != SPLC_LAYOUT_FLAT && layout != SPLC_LAYOUT_TILE64) return SPLC_EINVAL;
     if (capacity < 0 || (capacity > 0 && !out)) return SPLC_EINVAL;
     const bool tiled = layout == SPLC_LAYOUT_TILE64;
-    int64_t n_chunks = 0, n_params = 0;
-    std::vector<ChunkDesc> table;
     std::vector<int64_t> flat;
     if (!tiled && rows && cols && n_tensors >= 1) {               // flat layout: only the element counts matter
         flat.resize((size_t)n_tensors);
@@ -1202,14 +1495,22 @@ int64_t sparseloco_chunk_table(int n_tensors, const int64_t* rows, const int64_t
         }
         cols = flat.data();
     }
-    int rc = build_chunk_table(n_tensors, tiled ? rows : nullptr, cols, tiled, &n_chunks, &n_params,
-                               out ? &table : nullptr);
+    ChunkTables t;
+    int rc = build_chunk_tables(n_tensors, tiled ? rows : nullptr, cols, tiled, t, out != nullptr);
     if (rc != SPLC_OK) return rc;
     if (out) {
-        const int64_t n = n_chunks < capacity ? n_chunks : capacity;
-        std::copy(table.begin(), table.begin() + (ptrdiff_t)n, static_cast<ChunkDesc*>(out));
+        // the entries workgroups of the one-chunk kernels walk, then the members of the strips in strip order
+        std::vector<ChunkDesc> view = t.strips.empty() ? t.all : t.rest;
+        if (!t.strips.empty()) {
+            std::vector<const ChunkDesc*> by_id(t.all.size());
+            for (const ChunkDesc& cd : t.all) by_id[cd.id] = &cd;
+            for (const ChunkDesc& first : t.strips)
+                for (int j = 0; j < kStripTiles; ++j) view.push_back(*by_id[first.id + (uint32_t)j]);
+        }
+        const int64_t n = t.n_chunks < capacity ? t.n_chunks : capacity;
+        std::copy(view.begin(), view.begin() + (ptrdiff_t)n, static_cast<ChunkDesc*>(out));
     }
-    return n_chunks;
+    return t.n_chunks;
 }
 
 int sparseloco_tensors_bind(sparseloco_tensors** out, const sparseloco_plan* plan, int n_sets,
@@ -1392,8 +1693,8 @@ int sparseloco_outer_update(const sparseloco_plan* plan, const sparseloco_tensor
     if (theta_outer->n_sets != 1 || delta_bar->n_sets != 1 || !finite(outer_lr)) return SPLC_EINVAL;
     if ((rc = current_device_is(plan->device)) != SPLC_OK) return rc;
     if (plan->n_chunks == 0) return SPLC_OK;
-    hipLaunchKernelGGL(outer_update_kernel, dim3((unsigned)plan->n_chunks), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), plan->d_chunks, gen_entries(plan, false),
+    hipLaunchKernelGGL(outer_update_kernel, dim3((unsigned)plan->n_update), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), plan->d_update, (unsigned)plan->n_update_gen,
                        set_table<float*>(theta_outer, 0), set_table<const float*>(delta_bar, 0), outer_lr);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }

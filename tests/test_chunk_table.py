@@ -24,9 +24,26 @@ def check_table(shapes, tiled, batch=1024):
     expect_chunks = [(((r + 63) // 64) * ((c + 63) // 64) if (tiled and r > 1) else (r * c + 4095) // 4096) for r, c in rc]
     assert np.array_equal(np.bincount(tab["tensor"], minlength=len(shapes)), expect_chunks)
     assert int(tab["n_c"].sum()) == sum(numels)
-    # processing order: element-wise chunks first, then fp32-only vector chunks, then the rest
-    cls = np.where(tab["vec"] == 0, 0, np.where(tab["vec"] == 1, 1, 2))
+    # processing order of the chunks taken one by one: element-wise chunks first, then fp32-only vector chunks,
+    # then the rest; the members of four-tile strips follow, strip by strip
+    n_single = int((tab["strip"] == 0).sum())
+    single, members = tab[:n_single], tab[n_single:]
+    assert np.all(single["strip"] == 0)
+    cls = np.where(single["vec"] == 0, 0, np.where(single["vec"] == 1, 1, 2))
     assert np.all(np.diff(cls) >= 0) and set(np.unique(tab["vec"])) <= {0, 1, 3}
+    if not tiled:
+        assert len(members) == 0
+    assert len(members) % 4 == 0
+    if len(members):
+        m4 = members.reshape(-1, 4)
+        assert np.array_equal(m4["strip"], np.tile(np.arange(1, 5, dtype=np.uint32), (len(m4), 1)))
+        assert np.all(m4["vec"] == 3) and np.all(m4["n_c"] == 4096)            # complete tiles, even row length
+        assert np.all(m4["tensor"] == m4["tensor"][:, :1]) and np.all(m4["stride"] == m4["stride"][:, :1])
+        assert np.array_equal(m4["id"], m4["id"][:, :1] + np.arange(4, dtype=np.uint32))
+        assert np.array_equal(m4["offset"], m4["offset"][:, :1] + 64 * np.arange(4, dtype=np.uint64))
+        # a strip's rows (256 floats from the first tile's origin, 64 rows) stay inside the tensor
+        last = m4["offset"][:, 0].astype(np.int64) + 63 * m4["stride"][:, 0].astype(np.int64) + 255
+        assert np.all(last < np.asarray(numels, dtype=np.int64)[m4["tensor"][:, 0]])
     first = np.concatenate([[0], np.cumsum(expect_chunks)])
     for t, (r, c) in enumerate(rc):
         mine = by_id[first[t]:first[t + 1]]
@@ -92,6 +109,15 @@ def test_fuzzed_shapes(seed):
         shapes.append((5,))
     check_table(shapes, False)
     check_table(shapes, True)
+
+
+def test_strips_take_every_run_of_four_complete_tiles():
+    tab = B.chunk_table([(128, 1030), (130, 255), (64, 264), (64, 513), (7,), (64, 256)], True)
+    strips = tab[tab["strip"] == 1]
+    # 128 x 1030: 2 tile rows x 16 complete tiles -> 8 strips; 130 x 255: 3 complete tiles per row -> none;
+    # 64 x 264: one strip; 64 x 513: odd row length -> none; 64 x 256: rows are whole cache lines -> none
+    assert np.array_equal(np.bincount(strips["tensor"], minlength=6), [8, 0, 1, 0, 0, 0])
+    assert len(tab) == 2 * 17 + 3 * 4 + 5 + 9 + 1 + 4
 
 
 def test_rejections():

@@ -19,6 +19,10 @@ RAGGED = [4096 * 5, 4096 * 3 + 17, 100, 4096, 1, 2047, 4096 * 2 + 4, 0, 4096 * 2
 TILED_SHAPES = [(128, 192), (130, 70), (64, 64), (1, 5000), (63, 65), (200, 3), (3, 200), (65, 129), (1, 1), (70, 66)]
 
 
+# matrices wide enough for strips (four complete tiles taken by one workgroup), with leftovers and edges around them
+STRIP_SHAPES = [(128, 1030), (64, 264), (70, 520), (200, 322), (130, 255), (64, 513), (1, 3000), (66, 2050)]
+
+
 def gaussian_case(numels, R, seed, direct=None, heavy=False, shapes=None):
     """shapes: run with the 64 x 64 tile layout over these (rows, cols) matrices instead of flat chunks."""
     if shapes is not None:
@@ -52,14 +56,52 @@ def test_tiled_layout_params_mode(kappa, select):
     parity.check(case, kappa, select=select, what="tiled kappa=%d" % kappa)
 
 
+@pytest.mark.parametrize("select", [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX])
+@pytest.mark.parametrize("kappa", [1, 32, 64, 200, 300])
+def test_tiled_layout_with_strips(kappa, select):
+    """Runs of four complete tiles go to one 1024-lane workgroup: row lengths that are and are not multiples of
+    32 floats, leftover tiles at the end of a tile row, edge tiles below and to the right, odd row lengths (no
+    strips), with both selection algorithms and wide messages."""
+    case = gaussian_case(None, R=3, seed=700 + kappa, shapes=STRIP_SHAPES)
+    parity.check(case, kappa, select=select, what="strips kappa=%d" % kappa)
+
+
+@pytest.mark.parametrize("direct,quant,fused", [("f32", True, None), ("bf16", True, "no_mean"), ("bf16", False, "with_mean"),
+                                                (None, False, "with_mean")])
+def test_tiled_layout_with_strips_modes(direct, quant, fused):
+    case = gaussian_case(None, R=9, seed=731, direct=direct, heavy=True, shapes=STRIP_SHAPES)
+    parity.check(case, 48, lr=0.8, quant=quant, fused=fused, outer_steps=2, what="strips %s quant=%s" % (direct, quant))
+
+
+def test_strip_with_one_degenerate_tile():
+    """Inside one strip, one tile is constant (a 4096-way tie: the candidate filter gives up and the radix
+    select runs), one is all zero, one has few distinct values and one is ordinary: the four groups of the
+    workgroup must agree on the path and each still get its own tile right."""
+    rng = np.random.default_rng(9)
+    rows, cols = 64, 2 * 256 + 70
+    x = (rng.standard_normal((rows, cols)) * 1e-3).astype(np.float32)
+    x[:, 0:64] = -7.25
+    x[:, 64:128] = 0.0
+    x[:, 128:192] = (rng.integers(0, 3, (rows, 64)) * 0.125).astype(np.float32)
+    x[:, 256 + 64:256 + 128] = 3.0                       # second strip: one constant tile among ordinary ones
+    y = (rng.standard_normal((rows, cols)) * 1e-3).astype(np.float32)
+    th = [np.zeros(rows * cols, np.float32)]
+    ef = [[np.zeros(rows * cols, np.float32)] for _ in range(2)]
+    case = parity.HostCase(th, ef, delta=[[x.reshape(-1)], [y.reshape(-1)]], shapes=[(rows, cols)])
+    for kappa in (1, 32, 200):
+        parity.check(case, kappa, beta=1.0, what="degenerate strip kappa=%d" % kappa)
+        parity.check(case, kappa, beta=1.0, quant=False, fused="with_mean", what="degenerate strip, identity, kappa=%d" % kappa)
+
+
 @pytest.mark.parametrize("direct,quant", [("f32", True), ("bf16", True), ("bf16", False)])
 def test_tiled_layout_direct_modes(direct, quant):
     case = gaussian_case(None, R=2, seed=331, direct=direct, heavy=True, shapes=TILED_SHAPES)
     parity.check(case, 32, quant=quant, fused="no_mean", outer_steps=2, what="tiled direct %s" % direct)
 
 
-def test_tiled_layout_batched_and_fused():
-    case = gaussian_case(None, R=5, seed=337, shapes=TILED_SHAPES)
+@pytest.mark.parametrize("shapes", [TILED_SHAPES, STRIP_SHAPES], ids=["small", "strips"])
+def test_tiled_layout_batched_and_fused(shapes):
+    case = gaussian_case(None, R=5, seed=337, shapes=shapes)
     parity.check(case, 64, batch=True, fused="with_mean", outer_steps=2, what="tiled batched")
 
 
@@ -148,7 +190,7 @@ def test_fused_update_resets_the_replicas():
     """sparseloco_aggregate_update with reset tables: every theta_local becomes the new theta_outer, bit for
     bit, on flat and tiled layouts, full and edge chunks."""
     import torch
-    for shapes in (None, TILED_SHAPES):
+    for shapes in (None, TILED_SHAPES + STRIP_SHAPES[:4]):
         case = gaussian_case(RAGGED, R=3, seed=401, shapes=shapes)
         want = parity.run_oracle(case, 32, 0.95, 0.8)
         plan = B.Plan(case.shapes if shapes else case.numels, 32, True, tiled=shapes is not None)
@@ -274,7 +316,7 @@ def test_outer_step_replays_from_a_hip_graph(variant, tiled):
     replays, each after fresh local parameters were written by eager work and a synchronisation, each compared
     bit for bit with the same step run eagerly on a copy of the state; the first also against the oracle."""
     R, kappa, beta, lr = 5, 48, 0.95, 0.8
-    shapes = TILED_SHAPES if tiled else None
+    shapes = TILED_SHAPES + STRIP_SHAPES[:3] if tiled else None
     case = gaussian_case(RAGGED, R=R, seed=808, shapes=shapes)
     want = parity.run_oracle(case, kappa, beta, lr)
     plan = B.Plan(case.shapes if tiled else case.numels, kappa, True, tiled=tiled)
