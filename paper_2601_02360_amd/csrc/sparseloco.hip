@@ -290,20 +290,20 @@ __device__ void radix_select(SelectShared& sh, const float (&x)[16], int tid, ui
     __syncthreads();
 }
 
-// Top-kappa selection, quantiser, packing and residual for the chunk held in x[16] (already
-// folded).  On return x holds the new error-feedback values; the chunk's pairs, its levels (or
-// sent values) and its padding have been written.  All 256 lanes must call it; it ends with every
-// lane past its last read of `sh`, but callers that reuse `sh` must place a barrier first.
-template <int QUANT>
-__device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x)[16], int tid, int lane, int wave,
-                                                     uint32_t n_c, uint32_t pmask, uint32_t kappa, int force_radix,
-                                                     uint32_t* radix_counter, uint16_t* __restrict__ pairs_c,
-                                                     float* __restrict__ values_c, float* __restrict__ scales_c,
-                                                     uint32_t* group_ok = nullptr, int group = 0) {
-    // group_ok: four flags in LDS when four 256-lane groups of one workgroup each select a chunk of their own
-    // side by side (tid, lane, wave are then group-local and `sh` is the group's own).  Workgroup barriers must
-    // be reached by all groups alike, so the groups agree on the path: if one needs the radix select, all take it.
-    const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
+// Top-kappa selection of the chunk held in x[16] (already folded): finds the composite of the last kept entry
+// in (key descending, index ascending) order and publishes it in sh.thr, with the largest key (sh.wmax) and the
+// number of kept entries per 256-element bucket (sh.bucket).  Only the magnitudes of x are used, and only at the
+// start: a caller that can fetch its values again afterwards need not keep them in registers meanwhile.
+// All 256 lanes (of the group) must call it; it ends behind a workgroup barrier.
+// group_ok: four flags in LDS when four 256-lane groups of one workgroup each select a chunk of their own side
+// by side (tid, lane, wave are then group-local and `sh` is the group's own).  Workgroup barriers must be
+// reached by all groups alike, so the groups agree on the path: if one needs the radix select, all take it.
+// lds_chunk: if not null, the chunk sits in LDS in local index order and is read from there (x is ignored): once
+// for the keys, and again by the (rare) radix select, so that nothing but the keys stays in registers.
+__device__ __forceinline__ void find_threshold(SelectShared& sh, const float (&x)[16], int tid, int lane, int wave,
+                                               uint32_t kappa_c, uint32_t kappa, uint32_t pmask, int force_radix,
+                                               uint32_t* radix_counter, const float* lds_chunk = nullptr,
+                                               uint32_t* group_ok = nullptr, int group = 0) {
     sh.cand[tid] = 0;
     if (tid < 2) sh.cand[kCandCap + tid] = 0;
     if (tid < 16) sh.bucket[tid] = 0;
@@ -314,8 +314,19 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
     if (kappa <= (uint32_t)kFilterKappaMax && !force_radix) {
         // ---- candidate filter: a lower bound T0 of the threshold from the lane maxima ----
         uint32_t key[16];
+        if (lds_chunk) {
 #pragma unroll
-        for (int el = 0; el < 16; ++el) key[el] = __float_as_uint(x[el]) & 0x7FFFFFFFu;
+            for (int s = 0; s < 4; ++s) {
+                const float4 v = *reinterpret_cast<const float4*>(lds_chunk + s * 1024 + tid * 4);
+                key[4 * s] = __float_as_uint(v.x) & 0x7FFFFFFFu;
+                key[4 * s + 1] = __float_as_uint(v.y) & 0x7FFFFFFFu;
+                key[4 * s + 2] = __float_as_uint(v.z) & 0x7FFFFFFFu;
+                key[4 * s + 3] = __float_as_uint(v.w) & 0x7FFFFFFFu;
+            }
+        } else {
+#pragma unroll
+            for (int el = 0; el < 16; ++el) key[el] = __float_as_uint(x[el]) & 0x7FFFFFFFu;
+        }
         uint32_t tmax = 0;
 #pragma unroll
         for (int el = 0; el < 16; ++el) tmax = ((pmask >> el) & 1u) && key[el] > tmax ? key[el] : tmax;
@@ -388,10 +399,34 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
         __syncthreads();
     }
     if (!selected_by_filter) {
-        radix_select(sh, x, tid, pmask, kappa_c);
+        if (lds_chunk) {
+            // (the index is made opaque so that these reads are not merged with the caller's earlier ones, which
+            // would keep all sixteen values in registers from there to here)
+            int t = tid;
+            asm volatile("" : "+v"(t));
+            float y[16];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float4 v = *reinterpret_cast<const float4*>(lds_chunk + s * 1024 + t * 4);
+                y[4 * s] = v.x; y[4 * s + 1] = v.y; y[4 * s + 2] = v.z; y[4 * s + 3] = v.w;
+            }
+            radix_select(sh, y, tid, pmask, kappa_c);
+        } else {
+            radix_select(sh, x, tid, pmask, kappa_c);
+        }
         if (radix_counter && tid == 0) atomicAdd(radix_counter, 1u);      // diagnostic: chunks on the general path
     }
+}
 
+// Quantiser, packing and residual of the chunk held in x[16], given the threshold that find_threshold published
+// in `sh`.  On return x holds the new error-feedback values; the chunk's pairs, its levels (or sent values) and
+// its padding have been written.  It ends with every lane past its last read of `sh`, but callers that reuse
+// `sh` must place a barrier first.
+template <int QUANT>
+__device__ __forceinline__ void quantise_pack(const SelectShared& sh, float (&x)[16], int tid, int wave,
+                                              uint32_t kappa_c, uint32_t kappa, uint32_t pmask,
+                                              uint16_t* __restrict__ pairs_c, float* __restrict__ values_c,
+                                              float* __restrict__ scales_c) {
     // ---- final pass: selection predicate, output positions, quantise, pack, residual ----
     const uint64_t thr = sh.thr;
     const uint32_t T = (uint32_t)(thr >> 12);
@@ -460,6 +495,17 @@ __device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x
         scales_c[0] = lo;
         scales_c[1] = hi;
     }
+}
+
+// Both steps for a chunk that stays in registers throughout.
+template <int QUANT>
+__device__ __forceinline__ void select_quantise_pack(SelectShared& sh, float (&x)[16], int tid, int lane, int wave,
+                                                     uint32_t n_c, uint32_t pmask, uint32_t kappa, int force_radix,
+                                                     uint32_t* radix_counter, uint16_t* __restrict__ pairs_c,
+                                                     float* __restrict__ values_c, float* __restrict__ scales_c) {
+    const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
+    find_threshold(sh, x, tid, lane, wave, kappa_c, kappa, pmask, force_radix, radix_counter);
+    quantise_pack<QUANT>(sh, x, tid, wave, kappa_c, kappa, pmask, pairs_c, values_c, scales_c);
 }
 
 // The error-feedback buffer is rewritten densely (line 4 of the update equations).
@@ -554,6 +600,27 @@ struct StripShared {
 // Row-wise position of lane `lane` of wave `wave` (0..15) in round i (0..3): local row 16 i + wave of the strip,
 // floats 4 lane .. 4 lane + 3 of that row, i.e. tile lane / 16, local columns 4 (lane % 16) ...
 __device__ __forceinline__ uint32_t strip_row(int i, int wave) { return 16u * (uint32_t)i + (uint32_t)wave; }
+// Addressing of the row-wise accesses: per array one base that is uniform over the wave (the array's origin of
+// the strip plus `wave` rows), pinned into a scalar register pair, and per round i one 32-bit byte offset per
+// lane (16 i rows plus the lane's position in the row) that all arrays share.  Written out like this the accesses
+// are encoded as "scalar base + 32-bit lane offset"; left to itself the compiler keeps one 64-bit address per
+// access in vector registers, two dozen registers that the 64-register budget of this kernel does not have.
+template <class T>
+__device__ __forceinline__ T* strip_base(T* origin, const ChunkDesc& d, int wave) {
+    const uint64_t u = reinterpret_cast<uint64_t>(origin + (size_t)((uint32_t)wave * d.stride));
+    uint32_t lo = (uint32_t)u, hi = (uint32_t)(u >> 32);
+    asm volatile("" : "+s"(lo), "+s"(hi));
+    return reinterpret_cast<T*>(((uint64_t)hi << 32) | lo);
+}
+// Byte offset (for 4-byte elements) of this lane's four elements in round i; 63 rows * stride * 4 < 2^32.
+__device__ __forceinline__ uint32_t strip_offset(const ChunkDesc& d, int i, int lane) {
+    return ((uint32_t)(16 * i) * d.stride + (uint32_t)lane * 4u) * 4u;
+}
+template <class T>
+__device__ __forceinline__ T* strip_at(T* base, uint32_t offset_for_4_byte_elements) {
+    using Byte = typename std::conditional<std::is_const<T>::value, const char, char>::type;
+    return reinterpret_cast<T*>(reinterpret_cast<Byte*>(base) + offset_for_4_byte_elements / (4u / (uint32_t)sizeof(T)));
+}
 
 template <int MODE, int QUANT>
 __global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const ChunkDesc* __restrict__ strips,
@@ -569,23 +636,26 @@ __global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // 0..15
     const ChunkDesc d = strips[blockIdx.x];
-    float* const pe = ef_tab[d.tensor] + d.offset;
+    float* const pe = strip_base(ef_tab[d.tensor] + d.offset, d, wave);
     const uint32_t q = (uint32_t)lane >> 4, lc = ((uint32_t)lane & 15u) * 4u;
+    uint32_t off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) off[i] = strip_offset(d, i, lane);
 
     // ---- rows in: fold in registers, e' to LDS ----
     {
         float4 ev[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ev[i] = stream_load4(pe + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+        for (int i = 0; i < 4; ++i) ev[i] = stream_load4(strip_at<const float>(pe, off[i]));
         float x[16];
         if (MODE == MODE_PARAMS_F32) {
-            const float* po = static_cast<const float*>(src_a[d.tensor]) + d.offset;
-            const float* pl = static_cast<const float*>(src_b[d.tensor]) + d.offset;
+            const float* po = strip_base(static_cast<const float*>(src_a[d.tensor]) + d.offset, d, wave);
+            const float* pl = strip_base(static_cast<const float*>(src_b[d.tensor]) + d.offset, d, wave);
             float4 ov[4], lv[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ov[i] = stream_load4(po + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+            for (int i = 0; i < 4; ++i) ov[i] = stream_load4(strip_at(po, off[i]));
 #pragma unroll
-            for (int i = 0; i < 4; ++i) lv[i] = stream_load4(pl + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+            for (int i = 0; i < 4; ++i) lv[i] = stream_load4(strip_at(pl, off[i]));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 x[4 * i + 0] = fold(beta, ev[i].x, __fsub_rn(ov[i].x, lv[i].x));
@@ -594,10 +664,10 @@ __global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const 
                 x[4 * i + 3] = fold(beta, ev[i].w, __fsub_rn(ov[i].w, lv[i].w));
             }
         } else if (MODE == MODE_DIRECT_F32) {
-            const float* pd = static_cast<const float*>(src_a[d.tensor]) + d.offset;
+            const float* pd = strip_base(static_cast<const float*>(src_a[d.tensor]) + d.offset, d, wave);
             float4 dv[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dv[i] = stream_load4(pd + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+            for (int i = 0; i < 4; ++i) dv[i] = stream_load4(strip_at(pd, off[i]));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 x[4 * i + 0] = fold(beta, ev[i].x, dv[i].x);
@@ -606,10 +676,10 @@ __global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const 
                 x[4 * i + 3] = fold(beta, ev[i].w, dv[i].w);
             }
         } else {
-            const uint16_t* pd = static_cast<const uint16_t*>(src_a[d.tensor]) + d.offset;
+            const uint16_t* pd = strip_base(static_cast<const uint16_t*>(src_a[d.tensor]) + d.offset, d, wave);
             uint2 dv[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dv[i] = stream_load4(pd + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+            for (int i = 0; i < 4; ++i) dv[i] = stream_load4(strip_at(pd, off[i]));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 x[4 * i + 0] = fold(beta, ev[i].x, __uint_as_float(dv[i].x << 16));
@@ -631,15 +701,23 @@ __global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const 
         const int gtid = tid & (kThreads - 1);
         const int gwave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
         const uint64_t c = (uint64_t)d.id + (uint64_t)group;
+        const uint32_t kappa_c = kappa < (uint32_t)kChunk ? kappa : (uint32_t)kChunk;
         float x[16];
+        auto fetch_tile = [&]() {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const float4 v = *reinterpret_cast<const float4*>(&sm.tile[group][s * 1024 + gtid * 4]);
-            x[4 * s] = v.x; x[4 * s + 1] = v.y; x[4 * s + 2] = v.z; x[4 * s + 3] = v.w;
-        }
-        select_quantise_pack<QUANT>(sm.sel[group], x, gtid, lane, gwave, (uint32_t)kChunk, 0xFFFFu, kappa, force_radix,
-                                    radix_counter, pairs_out + c * kappa, aux_out + c * kappa, aux_out + 2 * c,
-                                    sm.group_ok, group);
+            for (int s = 0; s < 4; ++s) {
+                const float4 v = *reinterpret_cast<const float4*>(&sm.tile[group][s * 1024 + gtid * 4]);
+                x[4 * s] = v.x; x[4 * s + 1] = v.y; x[4 * s + 2] = v.z; x[4 * s + 3] = v.w;
+            }
+        };
+        // The threshold search reads the tile from LDS by itself (it needs only the magnitudes); the values are
+        // fetched afterwards: 64 registers per lane (two of these workgroups per compute unit) do not hold values
+        // and keys side by side.
+        find_threshold(sm.sel[group], x, gtid, lane, gwave, kappa_c, kappa, 0xFFFFu, force_radix, radix_counter,
+                       &sm.tile[group][0], sm.group_ok, group);
+        fetch_tile();
+        quantise_pack<QUANT>(sm.sel[group], x, gtid, gwave, kappa_c, kappa, 0xFFFFu, pairs_out + c * kappa,
+                             aux_out + c * kappa, aux_out + 2 * c);
 #pragma unroll
         for (int s = 0; s < 4; ++s)
             *reinterpret_cast<float4*>(&sm.tile[group][s * 1024 + gtid * 4]) =
@@ -647,10 +725,13 @@ __global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const 
     }
     __syncthreads();
 
-    // ---- rows out ----
+    // ---- rows out (offsets recomputed here, from an opaque copy of the lane number, so that they are not
+    // carried in registers through the selection) ----
+    int l = lane;
+    asm volatile("" : "+v"(l));
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-        stream_store4(pe + (size_t)strip_row(i, wave) * d.stride + 4 * lane,
+        stream_store4(strip_at(pe, strip_offset(d, i, l)),
                       *reinterpret_cast<const float4*>(&sm.tile[q][strip_row(i, wave) * 64u + lc]));
 }
 
@@ -980,8 +1061,8 @@ __global__ __launch_bounds__(kStripThreads, 8) void aggregate_strip_kernel(const
     const int gwave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);
     const ChunkDesc d = strips[blockIdx.x];
     const uint32_t q = (uint32_t)lane >> 4, lc = ((uint32_t)lane & 15u) * 4u;
-    float* th = UPDATE ? theta_tab[d.tensor] + d.offset : nullptr;
-    float* po = dbar_tab ? dbar_tab[d.tensor] + d.offset : nullptr;
+    float* th = UPDATE ? strip_base(theta_tab[d.tensor] + d.offset, d, wave) : nullptr;
+    float* po = dbar_tab ? strip_base(dbar_tab[d.tensor] + d.offset, d, wave) : nullptr;
     float4* acc4 = reinterpret_cast<float4*>(&acc[group][0]);
 #pragma unroll
     for (int s = 0; s < 4; ++s) acc4[s * kThreads + gtid] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -1004,23 +1085,23 @@ __global__ __launch_bounds__(kStripThreads, 8) void aggregate_strip_kernel(const
     float4 tv[4];
     if (UPDATE) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) tv[i] = stream_load4(th + (size_t)strip_row(i, wave) * d.stride + 4 * lane);
+        for (int i = 0; i < 4; ++i) tv[i] = stream_load4(strip_at<const float>(th, strip_offset(d, i, lane)));
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const size_t at = (size_t)strip_row(i, wave) * d.stride + 4 * lane;
         float4 v = *reinterpret_cast<const float4*>(&acc[q][strip_row(i, wave) * 64u + lc]);
         v.x = __fdiv_rn(v.x, m); v.y = __fdiv_rn(v.y, m); v.z = __fdiv_rn(v.z, m); v.w = __fdiv_rn(v.w, m);
-        if (po) stream_store4(po + at, v);
+        if (po) stream_store4(strip_at(po, strip_offset(d, i, lane)), v);
         if (UPDATE) {
             float4 t = tv[i];
             t.x = __fsub_rn(t.x, __fmul_rn(eta, v.x));
             t.y = __fsub_rn(t.y, __fmul_rn(eta, v.y));
             t.z = __fsub_rn(t.z, __fmul_rn(eta, v.z));
             t.w = __fsub_rn(t.w, __fmul_rn(eta, v.w));
-            stream_store4(th + at, t);
+            stream_store4(strip_at(th, strip_offset(d, i, lane)), t);
             for (int r = 0; r < n_reset; ++r)
-                stream_store4(reset_tab[(size_t)r * n_tensors + d.tensor] + d.offset + at, t);
+                stream_store4(strip_at(strip_base(reset_tab[(size_t)r * n_tensors + d.tensor] + d.offset, d, wave),
+                                       strip_offset(d, i, lane)), t);
         }
     }
 }
