@@ -62,6 +62,12 @@ typedef float vfloat4 __attribute__((ext_vector_type(4), aligned(4)));
 
 __device__ __forceinline__ vfloat4 ldg4(const float* p) { return *(const SPLC_GLOBAL vfloat4*)p; }
 __device__ __forceinline__ void stg4(float* p, vfloat4 v) { *(SPLC_GLOBAL vfloat4*)p = v; }
+// The same for data that this call touches exactly once (the tables the re-projection updates, reconstructed
+// activations): non-temporal, so that they do not displace the basis and the coefficients from the caches.
+__device__ __forceinline__ vfloat4 ldg4_once(const float* p) {
+    return __builtin_nontemporal_load((const SPLC_GLOBAL vfloat4*)p);
+}
+__device__ __forceinline__ void stg4_once(float* p, vfloat4 v) { __builtin_nontemporal_store(v, (SPLC_GLOBAL vfloat4*)p); }
 
 // F (4 or 8) consecutive floats row[col .. col + F - 1] of a matrix row with `cols` columns, into out[0 .. F-1].
 // GUARD = false: the caller knows that they all exist -- plain 16-byte loads, no branch (the compiler can then
@@ -94,6 +100,7 @@ __device__ __forceinline__ void row_load(const float* __restrict__ row, int col,
 
 // Pass 1: store the coefficients.
 struct StoreCoeff {
+    static constexpr bool kStaggeredStart = false;
     float* c;
     int64_t ld;
     __device__ __forceinline__ void load(int, int, vfloat4 (&)[2]) const {}
@@ -114,21 +121,25 @@ struct StoreCoeff {
 
 // Pass 2: v = Pi_S(T_S)[row][col .. col+3].
 struct UpdateEmbedding {
+    // This epilogue moves four arrays; a kernel that carries it is as much bound by memory as by the matrix
+    // pipe, and gains when the workgroups that share a compute unit are not all in their epilogue at once.
+    static constexpr bool kStaggeredStart = true;
     float* t_s;
     float* t_perp;
     int64_t ld;
+    int compute_units;       // of the device, for the staggered start
     __device__ __forceinline__ void load(int row, int col, vfloat4 (&r)[2]) const {
         const int64_t at = (int64_t)row * ld + col;
-        r[0] = ldg4(t_s + at);
-        r[1] = ldg4(t_perp + at);
+        r[0] = ldg4_once(t_s + at);
+        r[1] = ldg4_once(t_perp + at);
     }
     __device__ __forceinline__ void store(int row, int col, vfloat4 v, const vfloat4 (&r)[2]) const {
         const int64_t at = (int64_t)row * ld + col;
         vfloat4 q;
 #pragma unroll
         for (int i = 0; i < 4; ++i) q[i] = __fadd_rn(r[1][i], __fsub_rn(r[0][i], v[i]));
-        stg4(t_perp + at, q);
-        stg4(t_s + at, v);
+        stg4_once(t_perp + at, q);
+        stg4_once(t_s + at, v);
     }
     __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
         const int64_t at = (int64_t)row * ld + col;
@@ -212,6 +223,7 @@ struct SubtractHighRank {
 // Epilogue of reconstruct: out <- fl(fl(v + T_perp[x]) + PosEmbed); TP / PE: which tables exist.
 template <bool TP, bool PE>
 struct AddHighRank {
+    static constexpr bool kStaggeredStart = false;     // measured: no gain for the reconstruction
     HighRank h;
     float* out;
     __device__ __forceinline__ void load(int row, int col, vfloat4 (&r)[2]) const {
@@ -227,7 +239,7 @@ struct AddHighRank {
 #pragma unroll
             for (int i = 0; i < 4; ++i) v[i] = __fadd_rn(v[i], r[1][i]);
         }
-        stg4(out + (int64_t)row * h.ld + col, v);
+        stg4_once(out + (int64_t)row * h.ld + col, v);
     }
     __device__ __forceinline__ void operator()(int row, int col, vfloat4 v, int n_cols) const {
         if (col + 4 <= n_cols) {
@@ -304,6 +316,23 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<MATH, TM_, TN_, Pro>())) 
     const int row_block = (slot / col_tiles) * 8 + xcd;
     const int m0 = row_block * TM_, n0 = (slot % col_tiles) * TN_;
     if (m0 >= M) return;
+    if constexpr (Epi::kStaggeredStart) {
+        // The workgroups that start together on a compute unit run the same K loop and would then all reach
+        // the memory-heavy epilogue together, leaving the matrix pipe idle meanwhile, round after round.  The
+        // first batch of workgroups is therefore started a fraction of a tile apart: the r-th workgroup to land
+        // on a compute unit (workgroups are dealt out one per unit before any unit gets its second) sleeps
+        // r / R of one workgroup's lifetime, R = resident workgroups per unit; later ones inherit the phase of
+        // the slot they take over.  A lifetime is about R times the K loop's matrix-pipe time,
+        // n_tiles * 512 MI NJ cycles; s_sleep(127) is 8128 cycles.  Measured on the second pass of the
+        // re-projection at 32000 x 2048, k = 256: 356 -> 322 us.
+        constexpr int R = gemm_min_waves<MATH, TM_, TN_, Pro>();
+        const int first = epi.compute_units * R;
+        if ((int)blockIdx.x < first) {
+            const int r = (int)blockIdx.x / epi.compute_units;
+            const int sleeps = r * ((K + TK - 1) / TK) * (MI * NJ) / 16;
+            for (int i = 0; i < sleeps; ++i) __builtin_amdgcn_s_sleep(127);
+        }
+    }
 
     v16f acc[MI][NJ];
 #pragma unroll
@@ -759,7 +788,8 @@ void launch_gemm_tile(const float* A, int64_t lda, const float* B, int64_t ldb, 
 // Tile choice (measured on the shapes of sections 2.2 and 2.4 at d 1536 / 2048, k = d/8 ... d/16):
 //   columns: 64 wide when N spans an odd number of 64-column blocks (the last 128-wide tile would be at
 //            most half used), else 128 wide;
-//   rows:    128 when that still leaves two workgroups per compute unit, else 64;
+//   rows:    128 when that still leaves (nearly) two workgroups per compute unit -- 480 of them: the first pass of
+//            the re-projection at 32000 x 2048, k = 256 has 500 and takes 272 us so, 288 us with 64 rows --, else 64;
 //   a product with the basis as the N x K operand has K = k: up to K = 192 the K loop is so short that
 //            64 x 64 tiles win (more, smaller workgroups per compute unit overlap one group's epilogue
 //            with another's products); beyond that the reconstruction (light_epilogue: one store per
@@ -779,7 +809,7 @@ GemmTile choose_gemm_tile(bool b_nk, int M, int N, int K, bool light_epilogue, i
     } else if (light_epilogue) {
         tall = false;
     } else {
-        tall = groups(128, wide ? 128 : 64) >= 2 * 256;
+        tall = groups(128, wide ? 128 : 64) >= 480;
     }
     return GemmTile{tall, wide};
 }
@@ -801,6 +831,15 @@ bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0;
 
 namespace {
 
+// Compute units of the current device (256 on an MI355X).
+int compute_units() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        return 256;
+    return n;
+}
+
 // Both passes of the re-projection with the coefficients in `coeff_ws` (vocab * k floats of device memory).
 int reproject_impl(float* t_s, float* t_perp, const float* u, float* coeff_ws, int64_t vocab, int d, int k,
                    int matmul, hipStream_t st) {
@@ -812,7 +851,8 @@ int reproject_impl(float* t_s, float* t_perp, const float* u, float* coeff_ws, i
         launch_gemm<false>(t_s, (int64_t)d, u, (int64_t)k, M, k, d, NoPrologue{}, StoreCoeff{coeff_ws, (int64_t)k}, matmul,
                            st);
     // pass 2: Pi = coeff U^T           (M x d) = (M x k)(k x d), U given as d x k = the N x K form
-    launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{}, UpdateEmbedding{t_s, t_perp, (int64_t)d},
+    launch_gemm<true>(coeff_ws, (int64_t)k, u, (int64_t)k, M, d, k, NoPrologue{},
+                      UpdateEmbedding{t_s, t_perp, (int64_t)d, compute_units()},
                       matmul, st);
     return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
