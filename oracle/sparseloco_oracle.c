@@ -13,7 +13,7 @@
  *
  * Readings where the paper is silent (all of them are restated in the design
  * notes of the repository):
- *   - chunk geometry.  The paper gives the chunk as "64 x 64 (4096 elements)"
+ *   - chunk geometry.  The paper gives the chunk size as 64 x 64, that is 4096 elements
  *     (section 3, training configuration; appendix hyper-parameter table).
  *     Two readings are implemented:
  *       flat   a chunk is `chunk` consecutive elements of the row-major

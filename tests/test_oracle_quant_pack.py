@@ -1,7 +1,7 @@
 """Pins for the 2-bit quantiser and the (index, code) pair format.
 
-The paper names Q() and never defines it (section 2.1; its experiments ran
-"without quantization"), so nothing here checks the rule against the paper:
+The paper names Q() and never defines it (section 2.1; section 3 says its experiments
+used no quantisation), so nothing here checks the rule against the paper:
 "parity unpinned" for that.  What is pinned is the rule as this repository
 reads it -- hand-computed cases with exactly representable numbers, the closed
 form for a zero range, the error bound d/4, and the bit layout of a pair.
