@@ -20,7 +20,8 @@ TILED_SHAPES = [(128, 192), (130, 70), (64, 64), (1, 5000), (63, 65), (200, 3), 
 
 
 # matrices wide enough for strips (four complete tiles taken by one workgroup), with leftovers and edges around them
-STRIP_SHAPES = [(128, 1030), (64, 264), (70, 520), (200, 322), (130, 255), (64, 513), (1, 3000), (66, 2050)]
+STRIP_SHAPES = [(128, 1030), (64, 264), (70, 520), (200, 322), (130, 254), (64, 513), (1, 3000), (66, 2050), (3, 258),
+                (65, 450)]
 
 
 def gaussian_case(numels, R, seed, direct=None, heavy=False, shapes=None):
