@@ -172,3 +172,27 @@ def test_beta_is_the_binary32_nearest_to_0_95():
     values, _ = send_everything(e0, 0.95, delta=[np.zeros(1, np.float32)])
     assert Fraction(float(values[0])) == rn(Fraction(0x733333 + 0x800000, 2 ** 24) * 3)
     assert f32(rn(Fraction(0x733333 + 0x800000, 2 ** 24) * 3)) == values[0]
+
+
+def test_heterogeneous_mean_carries_the_predicted_bias():
+    """The analysis of heterogeneous aggregation (end of section 2.4): with a fraction alpha of the replicas
+    sending the unbiased pseudo-gradient D and the others its projection onto a subspace, the mean is
+    D - (1 - alpha) B with B = D - proj(D).  Checked through the oracle's own compress (Q = identity, kappa = chunk,
+    so that every entry is sent) and aggregate; D, its projection and the mean are exact in binary32 here
+    (small dyadic values, M a power of two), so the identity must hold bit for bit."""
+    rng = np.random.default_rng(11)
+    n, chunk, M, n_full = 64, 16, 8, 2                       # alpha = 2/8
+    d_star = (rng.integers(-64, 65, n) / 64.0).astype(np.float32)
+    keep = np.arange(n) % 4 == 0                             # projection onto a coordinate subspace: exact
+    d_proj = np.where(keep, d_star, 0).astype(np.float32)
+    bias = (d_star - d_proj).astype(np.float32)
+    pairs, vals = [], []
+    for m in range(M):
+        ef = [np.zeros(n, np.float32)]
+        p, v = oracle.compress(ef, chunk, 1.0, delta=[d_star if m < n_full else d_proj], chunk=chunk, quant=False)
+        assert not ef[0].any()                               # everything was sent: the buffer is empty again
+        pairs.append(p), vals.append(v)
+    mean = oracle.aggregate([n], pairs, vals, chunk, chunk=chunk, quant=False)[0]
+    alpha = n_full / M
+    assert np.array_equal(mean, (d_star - (1 - alpha) * bias).astype(np.float32))
+    assert np.array_equal(mean, (alpha * d_star + (1 - alpha) * d_proj).astype(np.float32))
