@@ -752,7 +752,6 @@ __device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so,
                                                                   uint16_t* const* __restrict__ pairs_tab,
                                                                   float* const* __restrict__ aux_tab) {
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const ChunkDesc d = chunks[blockIdx.x];
     const uint64_t c = d.id;
