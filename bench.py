@@ -446,6 +446,9 @@ def main():
         B.sparseloco_compress_batch(plan, b_theta, b_src, b_ef, b_msgs, beta, stream=stream)
         B.sparseloco_aggregate_update(plan, b_msgs, b_theta, lr, stream=stream)
 
+    def one_launch_step():
+        B.sparseloco_outer_step_batch(plan, b_theta, b_src, b_ef, b_msgs, beta, lr, stream=stream)
+
     def timed(fn):
         for _ in range(args.warmup):
             fn()
@@ -476,7 +479,7 @@ def main():
     plan.set_radix_counter(None)
     radix_selections = int(counter.item())
 
-    ms_fused = ms_batched = ms_graph = None
+    ms_fused = ms_batched = ms_one = ms_graph = None
     stream_ref_gbs = probe_gbs = None
     if not args.only_headline:
         # the same outer step with line 5 in one pass (sparseloco_aggregate_update, no dense mean written):
@@ -486,6 +489,9 @@ def main():
         # chunk), line 5 fused.  Same inputs, same outputs; fewer bytes actually moved.
         if not rs.direct:
             ms_batched = timed(batched_step)
+            # ... and the whole step in one launch: every chunk goes from its first read to the update of
+            # theta_outer inside one workgroup
+            ms_one = timed(one_launch_step)
         # the three-call step recorded once into a HIP graph and replayed (the calls only enqueue kernels):
         # what a launch-bound small parameter set gains
         side = torch.cuda.Stream()
@@ -553,6 +559,9 @@ def main():
     if ms_batched is not None:
         print("all replicas in one compress launch (sparseloco_compress_batch) + fused line 5: %.4f ms per step"
               % ms_batched, file=sys.stderr, flush=True)
+    if ms_one is not None:
+        print("the whole outer step in one launch (sparseloco_outer_step_batch): %.4f ms per step" % ms_one,
+              file=sys.stderr, flush=True)
     if ms_graph is not None:
         print("three-call step replayed from a HIP graph: %.4f ms per step (%.1f %% of HBM peak)"
               % (ms_graph, 100 * gbs(total_bytes, ms_graph) / HBM_PEAK_GBS), file=sys.stderr, flush=True)
@@ -590,6 +599,9 @@ def main():
                    "batched_ms_per_step": ms_batched,
                    "batched_params_per_s": None if ms_batched is None else n / (ms_batched * 1e-3),
                    "batched_actual_bytes": (4 + 12 * R) * n + 8 * n + 2 * R * nch * (2 * cfg["kappa"] + 8),
+                   "one_launch_ms_per_step": ms_one,
+                   "one_launch_params_per_s": None if ms_one is None else n / (ms_one * 1e-3),
+                   "one_launch_actual_bytes": (8 + 12 * R) * n + R * nch * (2 * cfg["kappa"] + 8),
                    "graph_replay_ms_per_step": ms_graph},
         "roofline": {"bound": "hbm", "kernel": "compress_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,

@@ -240,6 +240,24 @@ int sparseloco_aggregate_update(const sparseloco_plan* plan, const sparseloco_me
                                 const sparseloco_tensors* theta_local_reset, void* stream);
 
 /*
+ * The whole outer step of a single-node simulation in one launch: lines 1-4 for the first
+ * n_replicas sets of theta_local / ef as in sparseloco_compress_batch, then line 5 as in
+ * sparseloco_aggregate_update over exactly those replicas' messages.  Results are bit-identical to
+ * the two calls in sequence (the messages are still written: they are outputs).  Every chunk is
+ * handled by one workgroup from its first read to the update of theta_outer, so the sent values
+ * are averaged where they are produced and theta_outer is read once and written once.
+ *   theta_outer: one set, updated in place.  delta_bar_out: may be NULL; if given (one set), the
+ *   dense mean is written.  reset_theta_local != 0: the new theta_outer is also written into
+ *   theta_local sets 0 .. n_replicas-1 (section 2.1, inner step: replicas restart from the
+ *   synchronised parameters).  1 <= n_replicas <= SPLC_MAX_REPLICAS.
+ */
+int sparseloco_outer_step_batch(const sparseloco_plan* plan, int n_replicas,
+                                const sparseloco_tensors* theta_outer, const sparseloco_tensors* theta_local,
+                                const sparseloco_tensors* ef, float beta, float outer_lr,
+                                const sparseloco_messages* messages_out,
+                                const sparseloco_tensors* delta_bar_out, int reset_theta_local, void* stream);
+
+/*
  * How the dense products of the matrix entry points below (sections 2.2 and 2.4;
  * the paper fixes no precision for them) are formed on the matrix cores: the
  * `matmul` argument of those calls.

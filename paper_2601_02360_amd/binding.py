@@ -36,6 +36,7 @@ EXPORTS = [
     "sparseloco_tensors_bind", "sparseloco_tensors_release", "sparseloco_messages_bind", "sparseloco_messages_release",
     "sparseloco_compress", "sparseloco_aggregate",
     "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
+    "sparseloco_outer_step_batch",
     "sparseloco_reproject_embedding", "sparseloco_reproject_embedding_noalloc", "sparseloco_subspace_project",
     "sparseloco_subspace_reconstruct", "sparseloco_subspace_kernel_choice", "sparseloco_strerror",
 ]
@@ -83,6 +84,7 @@ def lib():
             "sparseloco_messages_release": (None, [vp]),
             "sparseloco_compress": (i32, [vp, i32, vp, vp, vp, i32, f32, vp, vp, vp]),
             "sparseloco_compress_batch": (i32, [vp, i32, vp, vp, vp, f32, vp, vp]),
+            "sparseloco_outer_step_batch": (i32, [vp, i32, vp, vp, vp, f32, f32, vp, vp, i32, vp]),
             "sparseloco_aggregate": (i32, [vp, vp, vp, vp]),
             "sparseloco_outer_update": (i32, [vp, vp, vp, f32, vp]),
             "sparseloco_aggregate_update": (i32, [vp, vp, vp, f32, vp, vp, vp]),
@@ -413,6 +415,23 @@ def sparseloco_compress_batch(plan: Plan, theta_outer, theta_local, ef, messages
                                          e.handle, float(beta), m.handle, _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_compress_batch")
+
+
+def sparseloco_outer_step_batch(plan: Plan, theta_outer, theta_local, ef, messages_out, beta: float,
+                                outer_lr: float, *, aux_out=None, delta_bar_out=None, reset: bool = False,
+                                n_replicas: Optional[int] = None, stream=None) -> None:
+    """The whole outer step of a single-node simulation in one launch: sparseloco_compress_batch followed by
+    sparseloco_aggregate_update over the same replicas, bit for bit.  reset=True also writes the new theta_outer
+    into the replicas' theta_local."""
+    tl, e = plan._tensors(theta_local, stream=stream), plan._tensors(ef, stream=stream)
+    m = plan._messages(messages_out, aux_out, stream)
+    n = tl.n_sets if n_replicas is None else int(n_replicas)
+    rc = lib().sparseloco_outer_step_batch(plan.handle, n, _h(plan._tensors(theta_outer, stream=stream)), tl.handle,
+                                           e.handle, float(beta), float(outer_lr), m.handle,
+                                           _h(plan._tensors(delta_bar_out, stream=stream)), 1 if reset else 0,
+                                           _stream(stream))
+    if rc != SPLC_OK:
+        raise SparseLoCoError(rc, "sparseloco_outer_step_batch")
 
 
 def sparseloco_stream_probe(pattern: int, a, b, c, sink, *, stream=None) -> None:

@@ -422,11 +422,13 @@ __device__ __forceinline__ void find_threshold(SelectShared& sh, const float (&x
 // in `sh`.  On return x holds the new error-feedback values; the chunk's pairs, its levels (or sent values) and
 // its padding have been written.  It ends with every lane past its last read of `sh`, but callers that reuse
 // `sh` must place a barrier first.
-template <int QUANT>
-__device__ __forceinline__ void quantise_pack(const SelectShared& sh, float (&x)[16], int tid, int wave,
-                                              uint32_t kappa_c, uint32_t kappa, uint32_t pmask,
-                                              uint16_t* __restrict__ pairs_c, float* __restrict__ values_c,
-                                              float* __restrict__ scales_c) {
+// With SUM, every sent value is also added to sum[index in the chunk] (LDS; an element is only ever touched by
+// the lane that holds it, so replicas that follow each other in one workgroup need no synchronisation for it).
+template <int QUANT, bool SUM>
+__device__ __forceinline__ void quantise_pack_sum(const SelectShared& sh, float (&x)[16], float* sum, int tid,
+                                                  int wave, uint32_t kappa_c, uint32_t kappa, uint32_t pmask,
+                                                  uint16_t* __restrict__ pairs_c, float* __restrict__ values_c,
+                                                  float* __restrict__ scales_c) {
     // ---- final pass: selection predicate, output positions, quantise, pack, residual ----
     const uint64_t thr = sh.thr;
     const uint32_t T = (uint32_t)(thr >> 12);
@@ -476,10 +478,12 @@ __device__ __forceinline__ void quantise_pack(const SelectShared& sh, float (&x)
                         uint32_t sign = bits >> 31;
                         float q = __uint_as_float(__float_as_uint(upper ? hi : lo) | (bits & 0x80000000u));
                         pairs_c[pos] = (uint16_t)(idx | (((sign << 1) | upper) << 12));
+                        if (SUM) sum[idx] = __fadd_rn(sum[idx], q);
                         x[4 * s + j] = __fsub_rn(x[4 * s + j], q);
                     } else {
                         pairs_c[pos] = (uint16_t)idx;
                         values_c[pos] = x[4 * s + j];
+                        if (SUM) sum[idx] = __fadd_rn(sum[idx], x[4 * s + j]);
                         x[4 * s + j] = __fsub_rn(x[4 * s + j], x[4 * s + j]);
                     }
                     ++pos;
@@ -495,6 +499,14 @@ __device__ __forceinline__ void quantise_pack(const SelectShared& sh, float (&x)
         scales_c[0] = lo;
         scales_c[1] = hi;
     }
+}
+
+template <int QUANT>
+__device__ __forceinline__ void quantise_pack(const SelectShared& sh, float (&x)[16], int tid, int wave,
+                                              uint32_t kappa_c, uint32_t kappa, uint32_t pmask,
+                                              uint16_t* __restrict__ pairs_c, float* __restrict__ values_c,
+                                              float* __restrict__ scales_c) {
+    quantise_pack_sum<QUANT, false>(sh, x, nullptr, tid, wave, kappa_c, kappa, pmask, pairs_c, values_c, scales_c);
 }
 
 // Both steps for a chunk that stays in registers throughout.
@@ -739,23 +751,30 @@ __global__ __launch_bounds__(kStripThreads, 8) void compress_strip_kernel(const 
 // workgroup reads its theta_outer chunk once and walks the replicas, so theta_outer costs 4 bytes
 // per parameter per launch instead of per replica.  Per replica the arithmetic, the selection and
 // the outputs are those of compress_kernel.
+// With STEP the workgroup finishes the outer step for its chunk (line 5): what each replica sends is
+// added, replica after replica, to a sum in LDS (an element always sits in the same lane, so the mean needs
+// neither the messages nor any synchronisation), and after the last replica the chunk's mean is applied to
+// theta_outer, written to delta_bar if asked for, and the new parameters are copied to the replicas'
+// theta_local if asked for.  The sums start at +0 and are divided once by M: the bits of
+// sparseloco_aggregate_update.
 // Table layout (device): theta_local[r][t] at tl_tab[r * n_tensors + t], likewise ef_tab; message
 // buffers pairs_tab[r], aux_tab[r].
-template <int QUANT, bool VEC>
-__device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so, const ChunkDesc* __restrict__ chunks,
-                                                                  int n_replicas, uint32_t n_tensors,
-                                                                  const float* const* __restrict__ to_tab,
-                                                                  const float* const* __restrict__ tl_tab,
-                                                                  float* const* __restrict__ ef_tab, float beta,
-                                                                  uint32_t kappa, int force_radix,
-                                                                  uint32_t* radix_counter,
-                                                                  uint16_t* const* __restrict__ pairs_tab,
-                                                                  float* const* __restrict__ aux_tab) {
+template <int QUANT, bool VEC, bool STEP>
+__device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so, float* sum,
+                                                    const ChunkDesc* __restrict__ chunks,
+                                                    int n_replicas, uint32_t n_tensors,
+                                                    float* const* __restrict__ to_tab, float* const* __restrict__ tl_tab,
+                                                    float* const* __restrict__ ef_tab, float beta, uint32_t kappa,
+                                                    int force_radix, uint32_t* radix_counter,
+                                                    uint16_t* const* __restrict__ pairs_tab,
+                                                    float* const* __restrict__ aux_tab, float eta,
+                                                    float* const* __restrict__ dbar_tab, int reset) {
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const ChunkDesc d = chunks[blockIdx.x];
     const uint64_t c = d.id;
     const uint32_t n_c = VEC ? (uint32_t)kChunk : d.n_c;
+    const uint32_t kappa_c = kappa < n_c ? kappa : n_c;
     const float* po = to_tab[d.tensor] + d.offset;
     const uint32_t pmask0 = VEC ? 0xFFFFu : present_mask(d, tid);
 
@@ -771,6 +790,11 @@ __device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so,
             const uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
             so[idx] = (pmask0 & (1u << el)) ? po[elem_of(d, idx)] : 0.f;
         }
+    }
+    float4* sum4 = reinterpret_cast<float4*>(sum);
+    if (STEP) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) sum4[s * kThreads + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
     for (int r = 0; r < n_replicas; ++r) {
         // Per-lane index arithmetic is recomputed in every round: hoisting it out of the loop would
@@ -804,31 +828,69 @@ __device__ __forceinline__ void compress_batch_body(SelectShared& sh, float* so,
             }
         }
         float* aux_r = aux_tab[r];
-        select_quantise_pack<QUANT>(sh, x, t, t & 63, wave, n_c, pmask, kappa, force_radix, radix_counter,
-                                    pairs_tab[r] + c * kappa, aux_r + c * kappa, aux_r + 2 * c);
+        find_threshold(sh, x, t, t & 63, wave, kappa_c, kappa, pmask, force_radix, radix_counter);
+        quantise_pack_sum<QUANT, STEP>(sh, x, sum, t, wave, kappa_c, kappa, pmask, pairs_tab[r] + c * kappa,
+                                       aux_r + c * kappa, aux_r + 2 * c);
         store_ef<VEC>(pe, d, t, pmask, x);
         __syncthreads();          // every lane is done with `sh` before the next replica re-initialises it
     }
+    if (!STEP) return;
+
+    const float m = (float)n_replicas;
+    float* th = to_tab[d.tensor] + d.offset;
+    float* pd = dbar_tab ? dbar_tab[d.tensor] + d.offset : nullptr;
+    const int n_reset = reset ? n_replicas : 0;
+    if (VEC) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float4 v = sum4[s * kThreads + tid], tn = so4[s * kThreads + tid];
+            v.x = __fdiv_rn(v.x, m); v.y = __fdiv_rn(v.y, m); v.z = __fdiv_rn(v.z, m); v.w = __fdiv_rn(v.w, m);
+            if (pd) stream_store4(vec_at(pd, d, tid, s), v);
+            tn.x = __fsub_rn(tn.x, __fmul_rn(eta, v.x));
+            tn.y = __fsub_rn(tn.y, __fmul_rn(eta, v.y));
+            tn.z = __fsub_rn(tn.z, __fmul_rn(eta, v.z));
+            tn.w = __fsub_rn(tn.w, __fmul_rn(eta, v.w));
+            stream_store4(vec_at(th, d, tid, s), tn);
+            for (int r = 0; r < n_reset; ++r)
+                stream_store4(vec_at(tl_tab[(size_t)r * n_tensors + d.tensor] + d.offset, d, tid, s), tn);
+        }
+    } else {
+#pragma unroll
+        for (int el = 0; el < 16; ++el) {
+            if (!(pmask0 & (1u << el))) continue;
+            const uint32_t idx = (el >> 2) * 1024 + tid * 4 + (el & 3);
+            const uint32_t at = elem_of(d, idx);
+            const float v = __fdiv_rn(sum[idx], m);
+            if (pd) pd[at] = v;
+            const float tn = __fsub_rn(so[idx], __fmul_rn(eta, v));
+            th[at] = tn;
+            for (int r = 0; r < n_reset; ++r) tl_tab[(size_t)r * n_tensors + d.tensor][d.offset + at] = tn;
+        }
+    }
 }
 
-template <int QUANT>
-__global__ __launch_bounds__(kThreads) void compress_batch_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n_gen,
+// Four workgroups per compute unit: the register allocation is held to 128.
+template <int QUANT, bool STEP>
+__global__ __launch_bounds__(kThreads, 4) void compress_batch_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n_gen,
                                                                   int n_replicas, uint32_t n_tensors,
-                                                                  const float* const* __restrict__ to_tab,
-                                                                  const float* const* __restrict__ tl_tab,
+                                                                  float* const* __restrict__ to_tab,
+                                                                  float* const* __restrict__ tl_tab,
                                                                   float* const* __restrict__ ef_tab, float beta,
                                                                   uint32_t kappa, int force_radix,
                                                                   uint32_t* radix_counter,
                                                                   uint16_t* const* __restrict__ pairs_tab,
-                                                                  float* const* __restrict__ aux_tab) {
+                                                                  float* const* __restrict__ aux_tab, float eta,
+                                                                  float* const* __restrict__ dbar_tab, int reset) {
     __shared__ __align__(16) SelectShared sh;
     __shared__ __align__(16) float so[kChunk];
+    __shared__ __align__(16) float sum[STEP ? kChunk : 4];
     if (blockIdx.x >= n_gen)
-        compress_batch_body<QUANT, true>(sh, so, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta, kappa,
-                                         force_radix, radix_counter, pairs_tab, aux_tab);
+        compress_batch_body<QUANT, true, STEP>(sh, so, sum, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta, kappa,
+                                               force_radix, radix_counter, pairs_tab, aux_tab, eta, dbar_tab, reset);
     else
-        compress_batch_body<QUANT, false>(sh, so, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta, kappa,
-                                          force_radix, radix_counter, pairs_tab, aux_tab);
+        compress_batch_body<QUANT, false, STEP>(sh, so, sum, chunks, n_replicas, n_tensors, to_tab, tl_tab, ef_tab, beta,
+                                                kappa, force_radix, radix_counter, pairs_tab, aux_tab, eta, dbar_tab,
+                                                reset);
 }
 
 // Line 5, first half: sum of the decoded messages of one chunk into a dense LDS accumulator.
@@ -1257,16 +1319,55 @@ void launch_compress(const sparseloco_plan* plan, const void* const* a, const vo
                            (uint32_t)plan->kappa, force_radix, plan->radix_counter, pairs_out, aux_out);
 }
 
-template <int QUANT>
-void launch_compress_batch(const sparseloco_plan* plan, int n_replicas, const float* const* to,
-                           const float* const* tl, float* const* ef, float beta, uint16_t* const* pairs,
-                           float* const* aux, hipStream_t stream) {
+template <int QUANT, bool STEP>
+void launch_compress_batch(const sparseloco_plan* plan, int n_replicas, float* const* to, float* const* tl,
+                           float* const* ef, float beta, uint16_t* const* pairs, float* const* aux, float eta,
+                           float* const* dbar, int reset, hipStream_t stream) {
     // Strips are taken tile by tile here: a strip entry is followed, in the device table, by nothing this kernel
     // could use, so the batched path walks the per-chunk view kept behind the update table.
-    hipLaunchKernelGGL((compress_batch_kernel<QUANT>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
+    hipLaunchKernelGGL((compress_batch_kernel<QUANT, STEP>), dim3((unsigned)plan->n_chunks), dim3(kThreads), 0, stream,
                        plan->d_all, (unsigned)plan->n_all_gen, n_replicas, (uint32_t)plan->n_tensors, to, tl, ef,
                        beta, (uint32_t)plan->kappa, plan->select == SPLC_SELECT_RADIX ? 1 : 0, plan->radix_counter, pairs,
-                       aux);
+                       aux, eta, dbar, reset);
+}
+
+// Shared by sparseloco_compress_batch and sparseloco_outer_step_batch.
+int compress_batch_impl(const sparseloco_plan* plan, int n_replicas, const sparseloco_tensors* theta_outer,
+                        const sparseloco_tensors* theta_local, const sparseloco_tensors* ef, float beta,
+                        const sparseloco_messages* messages_out, bool step, float outer_lr,
+                        const sparseloco_tensors* delta_bar_out, int reset, void* stream) {
+    if (!plan || n_replicas < 1 || n_replicas > SPLC_MAX_REPLICAS) return SPLC_EINVAL;
+    int rc;
+    if ((rc = check_tensors(plan, theta_outer, SPLC_F32, 1)) != SPLC_OK) return rc;
+    if (theta_outer->n_sets != 1) return SPLC_EINVAL;
+    if ((rc = check_tensors(plan, theta_local, SPLC_F32, n_replicas)) != SPLC_OK) return rc;
+    if ((rc = check_tensors(plan, ef, SPLC_F32, n_replicas)) != SPLC_OK) return rc;
+    if ((rc = check_messages(plan, messages_out, n_replicas)) != SPLC_OK) return rc;
+    if (delta_bar_out) {
+        if ((rc = check_tensors(plan, delta_bar_out, SPLC_F32, 1)) != SPLC_OK) return rc;
+        if (delta_bar_out->n_sets != 1) return SPLC_EINVAL;
+    }
+    if (!finite(beta) || !finite(outer_lr)) return SPLC_EINVAL;
+    if ((rc = current_device_is(plan->device)) != SPLC_OK) return rc;
+    if (plan->n_chunks == 0) return SPLC_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* const* d_to = set_table<float*>(theta_outer, 0);
+    float* const* d_tl = reinterpret_cast<float* const*>(theta_local->d_table);
+    float* const* d_ef = reinterpret_cast<float* const*>(ef->d_table);
+    uint16_t* const* d_pairs = reinterpret_cast<uint16_t* const*>(messages_out->d_table);
+    float* const* d_aux = reinterpret_cast<float* const*>(messages_out->d_table + messages_out->n_replicas);
+    float* const* d_dbar = delta_bar_out ? set_table<float*>(delta_bar_out, 0) : nullptr;
+    const bool q2 = plan->quant == SPLC_QUANT_2BIT;
+    if (q2 && !step)
+        launch_compress_batch<SPLC_QUANT_2BIT, false>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, 0.f, nullptr, 0, st);
+    else if (q2)
+        launch_compress_batch<SPLC_QUANT_2BIT, true>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, outer_lr, d_dbar, reset, st);
+    else if (!step)
+        launch_compress_batch<SPLC_QUANT_NONE, false>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, 0.f, nullptr, 0, st);
+    else
+        launch_compress_batch<SPLC_QUANT_NONE, true>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, outer_lr, d_dbar, reset, st);
+    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
 }
 
 template <int QUANT, int UPDATE>
@@ -1728,28 +1829,16 @@ int sparseloco_compress(const sparseloco_plan* plan, int delta_mode, const spars
 int sparseloco_compress_batch(const sparseloco_plan* plan, int n_replicas, const sparseloco_tensors* theta_outer,
                               const sparseloco_tensors* theta_local, const sparseloco_tensors* ef, float beta,
                               const sparseloco_messages* messages_out, void* stream) {
-    if (!plan || n_replicas < 1 || n_replicas > SPLC_MAX_REPLICAS) return SPLC_EINVAL;
-    int rc;
-    if ((rc = check_tensors(plan, theta_outer, SPLC_F32, 1)) != SPLC_OK) return rc;
-    if (theta_outer->n_sets != 1) return SPLC_EINVAL;
-    if ((rc = check_tensors(plan, theta_local, SPLC_F32, n_replicas)) != SPLC_OK) return rc;
-    if ((rc = check_tensors(plan, ef, SPLC_F32, n_replicas)) != SPLC_OK) return rc;
-    if ((rc = check_messages(plan, messages_out, n_replicas)) != SPLC_OK) return rc;
-    if (!finite(beta)) return SPLC_EINVAL;
-    if ((rc = current_device_is(plan->device)) != SPLC_OK) return rc;
-    if (plan->n_chunks == 0) return SPLC_OK;
+    return compress_batch_impl(plan, n_replicas, theta_outer, theta_local, ef, beta, messages_out, false, 0.f, nullptr, 0,
+                               stream);
+}
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const float* const* d_to = set_table<const float*>(theta_outer, 0);
-    const float* const* d_tl = reinterpret_cast<const float* const*>(theta_local->d_table);
-    float* const* d_ef = reinterpret_cast<float* const*>(ef->d_table);
-    uint16_t* const* d_pairs = reinterpret_cast<uint16_t* const*>(messages_out->d_table);
-    float* const* d_aux = reinterpret_cast<float* const*>(messages_out->d_table + messages_out->n_replicas);
-    if (plan->quant == SPLC_QUANT_2BIT)
-        launch_compress_batch<SPLC_QUANT_2BIT>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
-    else
-        launch_compress_batch<SPLC_QUANT_NONE>(plan, n_replicas, d_to, d_tl, d_ef, beta, d_pairs, d_aux, st);
-    return hipGetLastError() == hipSuccess ? SPLC_OK : SPLC_EHIP;
+int sparseloco_outer_step_batch(const sparseloco_plan* plan, int n_replicas, const sparseloco_tensors* theta_outer,
+                                const sparseloco_tensors* theta_local, const sparseloco_tensors* ef, float beta,
+                                float outer_lr, const sparseloco_messages* messages_out,
+                                const sparseloco_tensors* delta_bar_out, int reset_theta_local, void* stream) {
+    return compress_batch_impl(plan, n_replicas, theta_outer, theta_local, ef, beta, messages_out, true, outer_lr,
+                               delta_bar_out, reset_theta_local ? 1 : 0, stream);
 }
 
 int sparseloco_aggregate(const sparseloco_plan* plan, const sparseloco_messages* messages,

@@ -88,7 +88,9 @@ def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AU
             deltas_per_step=None, stream: Optional[torch.cuda.Stream] = None, fused=None, batch=False):
     """fused: None = aggregate then outer_update; "with_mean" / "no_mean" = sparseloco_aggregate_update
     with / without the dense mean output (without it, the returned mean is recomputed by a separate
-    sparseloco_aggregate call, which the fused call must agree with anyway)."""
+    sparseloco_aggregate call, which the fused call must agree with anyway).
+    batch: False = one compress launch per replica; True = sparseloco_compress_batch; "step" = the whole outer
+    step in one launch (sparseloco_outer_step_batch; its mean output follows `fused` as above)."""
     ctx = torch.cuda.stream(stream) if stream is not None else torch.cuda.stream(torch.cuda.current_stream())
     out = []
     with ctx:
@@ -106,7 +108,12 @@ def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AU
                 p.fill_(0x5A5A)
                 a.fill_(float("nan"))
             b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
-            if batch:
+            dbar = [torch.full((n,), float("nan"), device="cuda") for n in case.numels]
+            b_dbar = plan.bind(dbar)
+            if batch == "step":                     # the whole step in one launch
+                B.sparseloco_outer_step_batch(plan, b_th, b_tl, b_ef, b_msgs, beta, lr,
+                                              delta_bar_out=b_dbar if fused == "with_mean" else None)
+            elif batch:
                 B.sparseloco_compress_batch(plan, b_th, b_tl, b_ef, b_msgs, beta)
             for r in range(case.R if not batch else 0):
                 p, a = msgs[r]
@@ -116,9 +123,10 @@ def run_gpu(case: HostCase, kappa, beta, lr, quant=True, select=B.SPLC_SELECT_AU
                     B.sparseloco_compress(plan, b_ef, p, a, beta, delta=d, replica=r)
                 else:
                     B.sparseloco_compress(plan, b_ef, p, a, beta, theta_outer=b_th, theta_local=b_tl, replica=r)
-            dbar = [torch.full((n,), float("nan"), device="cuda") for n in case.numels]
-            b_dbar = plan.bind(dbar)
-            if fused is None:
+            if batch == "step":
+                if fused != "with_mean":
+                    B.sparseloco_aggregate(plan, b_msgs, b_dbar)
+            elif fused is None:
                 B.sparseloco_aggregate(plan, b_msgs, b_dbar)
                 B.sparseloco_outer_update(plan, b_th, b_dbar, lr)
             elif fused == "with_mean":

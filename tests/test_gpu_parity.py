@@ -187,6 +187,71 @@ def test_batched_compress_matches_the_oracle(kappa, R, quant, select):
     parity.check(case, kappa, quant=quant, select=select, batch=True, outer_steps=2, what="batched compress")
 
 
+@pytest.mark.parametrize("select", [B.SPLC_SELECT_AUTO, B.SPLC_SELECT_RADIX])
+@pytest.mark.parametrize("kappa,R,quant,fused", [(32, 1, True, "with_mean"), (64, 8, True, "no_mean"),
+                                                 (128, 5, False, "with_mean"), (300, 3, True, "no_mean"),
+                                                 (4096, 2, False, "with_mean"), (1, 9, True, "with_mean")])
+def test_one_launch_outer_step_matches_the_oracle(kappa, R, quant, fused, select):
+    case = gaussian_case(RAGGED, R=R, seed=900 + kappa + R, heavy=True)
+    parity.check(case, kappa, lr=0.8, quant=quant, select=select, batch="step", fused=fused, outer_steps=2,
+                 what="one-launch step")
+
+
+@pytest.mark.parametrize("shapes", [TILED_SHAPES, STRIP_SHAPES], ids=["small", "strips"])
+def test_one_launch_outer_step_tiled(shapes):
+    case = gaussian_case(None, R=5, seed=937, shapes=shapes)
+    parity.check(case, 64, batch="step", fused="with_mean", outer_steps=2, what="tiled one-launch step")
+
+
+@pytest.mark.parametrize("R", [33, 64])
+def test_one_launch_outer_step_many_replicas(R):
+    case = gaussian_case([4096 * 2 + 77, 300], R=R, seed=960 + R, heavy=True)
+    parity.check(case, 32, batch="step", fused="with_mean", what="one-launch step R=%d" % R)
+
+
+def test_one_launch_outer_step_equals_the_two_calls_and_resets():
+    """Bit for bit the outputs of sparseloco_compress_batch + sparseloco_aggregate_update (ties, zeros and constant
+    chunks included), and with reset every participating theta_local becomes the new theta_outer while a further
+    set of the binding is left alone."""
+    rng = np.random.default_rng(77)
+    numels = RAGGED + [4096 * 3]
+    th = [(rng.standard_normal(n) * 0.02).astype(np.float32) for n in numels]
+    R = 4
+    tl = [[(th[t] - np.round(rng.standard_normal(n) * 3).astype(np.float32) * 2.0 ** -12).astype(np.float32)
+           for t, n in enumerate(numels)] for _ in range(R)]                      # few distinct values: many ties
+    for r in range(R):
+        tl[r][-1][:4096] = th[-1][:4096]                                          # an all-zero chunk
+    ef = [[np.zeros(n, np.float32) for n in numels] for _ in range(R)]
+    for quant in (True, False):
+        plan = B.Plan(numels, 32, quant)
+        outs = []
+        for one_launch in (False, True):
+            g_th = [parity._dev(x) for x in th]
+            g_ef = [[parity._dev(x) for x in r] for r in ef]
+            g_tl = [[parity._dev(x) for x in r] for r in tl]
+            msgs = [plan.message_buffers() for _ in range(R)]
+            b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
+            b_tl = plan.bind(g_tl)
+            dbar = [torch.full((n,), float("nan"), device="cuda") for n in numels]
+            if one_launch:
+                B.sparseloco_outer_step_batch(plan, g_th, b_tl, g_ef, b_msgs, 0.95, 0.7, delta_bar_out=dbar, reset=True,
+                                              n_replicas=R - 1)
+            else:
+                B.sparseloco_compress_batch(plan, g_th, b_tl, g_ef, b_msgs, 0.95, n_replicas=R - 1)
+                first = plan.bind_messages([m[0] for m in msgs[:R - 1]], [m[1] for m in msgs[:R - 1]])
+                B.sparseloco_aggregate_update(plan, first, g_th, 0.7, delta_bar_out=dbar, reset=g_tl[:R - 1])
+            torch.cuda.synchronize()
+            outs.append([parity.to_np(x).tobytes() for x in g_th + dbar + [x for r in g_ef[:R - 1] for x in r]
+                         + [x for m in msgs[:R - 1] for x in m] + [x for r in g_tl for x in r]])
+            if one_launch:
+                for t in range(len(numels)):
+                    new = parity.to_np(g_th[t]).tobytes()
+                    assert all(parity.to_np(g_tl[r][t]).tobytes() == new for r in range(R - 1))
+                    assert parity.to_np(g_tl[R - 1][t]).tobytes() == tl[R - 1][t].tobytes()
+        assert outs[0] == outs[1]
+        plan.close()
+
+
 def test_fused_update_resets_the_replicas():
     """sparseloco_aggregate_update with reset tables: every theta_local becomes the new theta_outer, bit for
     bit, on flat and tiled layouts, full and edge chunks."""
@@ -310,7 +375,7 @@ def test_reset_of_64_replicas_on_ragged_tensors():
     plan.close()
 
 
-@pytest.mark.parametrize("variant", ["three_calls", "batched_fused"])
+@pytest.mark.parametrize("variant", ["three_calls", "batched_fused", "one_launch"])
 @pytest.mark.parametrize("tiled", [False, True])
 def test_outer_step_replays_from_a_hip_graph(variant, tiled):
     """The operations only enqueue kernels, so a whole outer step can be recorded into a HIP graph.  Three
@@ -339,9 +404,12 @@ def test_outer_step_replays_from_a_hip_graph(variant, tiled):
                                           theta_local=self.b_tl, replica=r)
                 B.sparseloco_aggregate(plan, self.b_msgs, self.b_dbar)
                 B.sparseloco_outer_update(plan, self.b_th, self.b_dbar, lr)
-            else:
+            elif variant == "batched_fused":
                 B.sparseloco_compress_batch(plan, self.b_th, self.b_tl, self.b_ef, self.b_msgs, beta)
                 B.sparseloco_aggregate_update(plan, self.b_msgs, self.b_th, lr, delta_bar_out=self.b_dbar)
+            else:
+                B.sparseloco_outer_step_batch(plan, self.b_th, self.b_tl, self.b_ef, self.b_msgs, beta, lr,
+                                              delta_bar_out=self.b_dbar)
 
         def tensors(self):
             return self.th + [x for r in self.ef for x in r] + [x for m in self.msgs for x in m] + self.dbar
@@ -442,6 +510,18 @@ def test_error_returns_do_not_launch():
     with pytest.raises(B.SparseLoCoError) as ei:        # replica index beyond the sets of a multi-set binding
         B.sparseloco_compress(plan, plan.bind([e, e]), p, a, 0.95, delta=e, replica=2)
     assert ei.value.status == B.SPLC_EINVAL
+    two = [plan.message_buffers() for _ in range(2)]
+    m2 = plan.bind_messages([m[0] for m in two], [m[1] for m in two])
+    th0 = [t.clone() for t in e]
+    for kwargs in (dict(n_replicas=3), dict(n_replicas=0)):      # more replicas than bound sets / messages; none
+        with pytest.raises(B.SparseLoCoError) as ei:
+            B.sparseloco_outer_step_batch(plan, th0, [e, e], plan.bind([e, e]), m2, 0.95, 1.0, **kwargs)
+        assert ei.value.status == B.SPLC_EINVAL
+    with pytest.raises(B.SparseLoCoError) as ei:
+        B.sparseloco_outer_step_batch(plan, th0, [e, e], plan.bind([e, e]), m2, 0.95, float("nan"))
+    assert ei.value.status == B.SPLC_EINVAL
+    torch.cuda.synchronize()
+    assert all(torch.equal(a_, b_) for a_, b_ in zip(th0, e))     # nothing was launched
     other = B.Plan([4096], 32)
     with pytest.raises(B.SparseLoCoError) as ei:        # a binding made for another plan
         B.sparseloco_outer_update(plan, other.bind([e[0]]), e, 1.0)
