@@ -95,7 +95,9 @@ def all_chunk_properties(plan, msg, numels, kappa):
     assert bool((s[:, 0] <= s[:, 1]).all()) and bool((s[:, 0] >= 0).all()) and bool(torch.isfinite(s).all())
 
 
-def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1, seed=0, tiled=False):
+def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1, seed=0, tiled=False,
+                   one_launch=False):
+    """one_launch: the step goes through sparseloco_outer_step_batch instead of the three calls."""
     cfg = W.WORKLOADS[workload]
     rs = W.ReplicaSet(workload, device="cuda", replicas=R, tensors=tensors)
     shapes = [W.tensor_shapes(workload)[t] for t in rs.tensor_ids] if tiled else None
@@ -120,14 +122,18 @@ def fullsize_check(workload, R, kappa, tensors=None, n_random=300, outer_steps=1
             tl0 = [gather_(rs.theta_local[r], picks) for r in range(R)]
         msgs = [plan.message_buffers() for _ in range(R)]
         b_msgs = plan.bind_messages([m[0] for m in msgs], [m[1] for m in msgs])
-        for r in range(R):
+        if one_launch:
+            B.sparseloco_outer_step_batch(plan, b_theta, b_tl, b_ef, b_msgs, cfg["beta"], cfg["outer_lr"],
+                                          delta_bar_out=b_dbar)
+        for r in range(0 if one_launch else R):
             if rs.direct:
                 B.sparseloco_compress(plan, b_ef, msgs[r][0], msgs[r][1], cfg["beta"], delta=rs.delta[r], replica=r)
             else:
                 B.sparseloco_compress(plan, b_ef, msgs[r][0], msgs[r][1], cfg["beta"],
                                       theta_outer=b_theta, theta_local=b_tl, replica=r)
-        B.sparseloco_aggregate(plan, b_msgs, b_dbar)
-        B.sparseloco_outer_update(plan, b_theta, b_dbar, cfg["outer_lr"])
+        if not one_launch:
+            B.sparseloco_aggregate(plan, b_msgs, b_dbar)
+            B.sparseloco_outer_update(plan, b_theta, b_dbar, cfg["outer_lr"])
         torch.cuda.synchronize()
         b_msgs.close()
         for r in (0, R - 1):
@@ -153,6 +159,16 @@ def test_workload2_full_size_as_benchmarked():
     """~0.9B parameters, kappa 64, R 8: the configuration bench.py times."""
     cfg = W.WORKLOADS[2]
     fullsize_check(2, cfg["replicas"], cfg["kappa"], n_random=400)
+
+
+def test_workload2_full_size_in_one_launch():
+    """The same configuration through sparseloco_outer_step_batch (bench.py's one-launch variant), two outer steps."""
+    cfg = W.WORKLOADS[2]
+    fullsize_check(2, cfg["replicas"], cfg["kappa"], n_random=300, outer_steps=2, seed=3, one_launch=True)
+
+
+def test_workload2_tiled_in_one_launch():
+    fullsize_check(2, 4, W.WORKLOADS[2]["kappa"], n_random=200, seed=4, tiled=True, one_launch=True)
 
 
 @pytest.mark.parametrize("kappa", [16, 32, 64, 128])
