@@ -22,14 +22,14 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     The operations (compress, compress_batch, outer_step_batch, aggregate,
  *     aggregate_update, outer_update and the matrix entry points) ONLY ENQUEUE
- *     KERNELS on it: no
- *     allocation, no copy, no event, no host wait.  They can be recorded into a
- *     HIP graph.  plan_create and the bind calls allocate and enqueue one small
+ *     KERNELS on it: no allocation, no copy, no event, no host wait.  They can
+ *     be recorded into a HIP graph.  plan_create and the bind calls allocate and enqueue one small
  *     host-to-device copy on their stream; work on ANOTHER stream that uses the
  *     plan or the handle must be ordered after that copy by the caller.
- *   - The plan and the handles are immutable once created (the one exception,
- *     sparseloco_plan_set_select / _set_radix_counter, are test switches) and belong to the device
- *     that was current when they were created; every operation takes them as
+ *   - The plan and the handles are immutable once created (the exceptions,
+ *     sparseloco_plan_set_select and sparseloco_plan_set_radix_counter, are test
+ *     and diagnostic switches) and belong to the device that was current when
+ *     they were created; every operation takes them as
  *     pointers to const and may be called from several host threads at once.
  *     Release a handle or destroy a plan only after the work that uses it has
  *     completed (the release calls free device memory, which waits for the
