@@ -279,7 +279,7 @@ def bench_stream(args):
     import torch
     from paper_2601_02360_amd import binding as B
     torch.cuda.set_device(0)
-    n = (args.stream_elems // 4096) * 4096
+    n = (args.stream_elems // (4096 * 2048)) * (4096 * 2048)     # whole runs of up to 256 chunks on every XCD
     a, b, c = (torch.empty(n, device="cuda").normal_() for _ in range(3))
     sink = torch.zeros(1, device="cuda")
     patterns = [("read", B.SPLC_STREAM_READ, 4), ("write", B.SPLC_STREAM_WRITE, 4), ("copy_1r1w", B.SPLC_STREAM_COPY, 8),
@@ -298,6 +298,27 @@ def bench_stream(args):
         ms = e0.elapsed_time(e1) / args.steps
         out[name] = {"ms": ms, "gbs": bpe * n / (ms * 1e-3) / 1e9}
         print("stream %-14s %8.3f ms  %7.0f GB/s" % (name, ms, out[name]["gbs"]), file=sys.stderr, flush=True)
+    # What the choices a kernel is free to make are worth, for the write-only stream and the compress pattern: the
+    # part of each array a workgroup covers, which XCD takes which chunks, how many workgroups share a compute unit.
+    shapes = [("16KB_per_group", dict()), ("4KB_per_group", dict(slots=1)),
+              ("xcd_runs_of_16", dict(run=16)), ("xcd_runs_of_256", dict(run=256)),
+              ("1_group_per_unit", dict(max_groups_per_unit=1)), ("2_groups_per_unit", dict(max_groups_per_unit=2)),
+              ("4_groups_per_unit", dict(max_groups_per_unit=4))]
+    shaped = {}
+    for name, pat, bpe in (patterns[1], patterns[4]):
+        shaped[name] = {}
+        for tag, kw in shapes:
+            for _ in range(args.warmup):
+                B.sparseloco_stream_probe(pat, a, b, c, sink, **kw)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                B.sparseloco_stream_probe(pat, a, b, c, sink, **kw)
+            e1.record()
+            torch.cuda.synchronize()
+            shaped[name][tag] = bpe * n / (e0.elapsed_time(e1) / args.steps * 1e-3) / 1e9
+        print("stream %-14s " % name + "  ".join("%s %.0f" % kv for kv in shaped[name].items()) + " GB/s",
+              file=sys.stderr, flush=True)
     # the library's elementwise kernel with the compress kernel's pattern, as an independent reference
     d = torch.empty_like(a)
     for _ in range(3):
@@ -316,7 +337,7 @@ def bench_stream(args):
               "ms_per_step": best["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
               "dtype": "f32", "data": "synthetic",
               "config": {"workload": "stream probes over %d-float arrays (%.2f GB each)" % (n, 4 * n / 1e9),
-                         "patterns": out, "wall_s": time.perf_counter() - t_all},
+                         "patterns": out, "launch_shapes_gbs": shaped, "wall_s": time.perf_counter() - t_all},
               "roofline": {"bound": "hbm", "kernel": "stream_kernel<3 reads + 1 write>", "achieved": best["gbs"],
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["gbs"] / HBM_PEAK_GBS, "traffic": None}}
     print(json.dumps(result), flush=True)

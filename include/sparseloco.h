@@ -358,6 +358,17 @@ int sparseloco_subspace_kernel_choice(int op, int64_t rows, int d, int k, int ta
 enum { SPLC_STREAM_READ = 0, SPLC_STREAM_WRITE = 1, SPLC_STREAM_COPY = 2, SPLC_STREAM_R2W1 = 3, SPLC_STREAM_R3W1 = 4 };
 int sparseloco_stream_probe(int pattern, const float* a, const float* b, float* c, float* sink, int64_t n,
                             void* stream);
+/*
+ * The same patterns with the launch shape varied:
+ *   slots                4 (the kernels' shape: a workgroup covers 16 KB of each array) or 1 (4 KB);
+ *   run                  0 = workgroup i takes chunk i (eight neighbouring chunks run on the eight XCDs); > 0 =
+ *                        every XCD walks runs of `run` consecutive chunks (the number of workgroups must then
+ *                        be a multiple of 8 * run);
+ *   max_groups_per_unit  0 = as many workgroups per compute unit as fit, else at most this many (1..8).
+ * sparseloco_stream_probe is (slots 4, run 0, max_groups_per_unit 0).
+ */
+int sparseloco_stream_probe_shaped(int pattern, const float* a, const float* b, float* c, float* sink, int64_t n,
+                                   int slots, int run, int max_groups_per_unit, void* stream);
 
 const char* sparseloco_strerror(int status);
 

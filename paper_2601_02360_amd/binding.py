@@ -33,6 +33,7 @@ EXPORTS = [
     "sparseloco_plan_layout", "sparseloco_plan_num_tensors",
     "sparseloco_plan_num_params", "sparseloco_plan_kappa", "sparseloco_plan_quant_mode",
     "sparseloco_plan_set_select", "sparseloco_plan_set_radix_counter", "sparseloco_chunk_table", "sparseloco_stream_probe",
+    "sparseloco_stream_probe_shaped",
     "sparseloco_tensors_bind", "sparseloco_tensors_release", "sparseloco_messages_bind", "sparseloco_messages_release",
     "sparseloco_compress", "sparseloco_aggregate",
     "sparseloco_outer_update", "sparseloco_aggregate_update", "sparseloco_compress_batch",
@@ -77,6 +78,7 @@ def lib():
             "sparseloco_plan_set_select": (i32, [vp, i32]),
             "sparseloco_plan_set_radix_counter": (i32, [vp, vp]),
             "sparseloco_stream_probe": (i32, [i32, vp, vp, vp, vp, i64, vp]),
+            "sparseloco_stream_probe_shaped": (i32, [i32, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
             "sparseloco_chunk_table": (i64, [i32, p64, p64, i32, vp, i64]),
             "sparseloco_tensors_bind": (i32, [pp, vp, i32, pp, i32, vp]),
             "sparseloco_tensors_release": (None, [vp]),
@@ -434,13 +436,16 @@ def sparseloco_outer_step_batch(plan: Plan, theta_outer, theta_local, ef, messag
         raise SparseLoCoError(rc, "sparseloco_outer_step_batch")
 
 
-def sparseloco_stream_probe(pattern: int, a, b, c, sink, *, stream=None) -> None:
-    """One launch of a streaming probe (SPLC_STREAM_*) over flat fp32 device tensors of equal length."""
+def sparseloco_stream_probe(pattern: int, a, b, c, sink, *, slots: int = 4, run: int = 0, max_groups_per_unit: int = 0,
+                            stream=None) -> None:
+    """One launch of a streaming probe (SPLC_STREAM_*) over flat fp32 device tensors of equal length; slots, run and
+    max_groups_per_unit vary the launch shape (sparseloco_stream_probe_shaped)."""
     n = next(t.numel() for t in (a, b, c) if t is not None)
     for t in (a, b, c):
         if t is not None and (t.numel() != n or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda):
             raise ValueError("probe arrays: contiguous fp32 GPU tensors of equal length")
-    rc = lib().sparseloco_stream_probe(int(pattern), _opt(a), _opt(b), _opt(c), _opt(sink), int(n), _stream(stream))
+    rc = lib().sparseloco_stream_probe_shaped(int(pattern), _opt(a), _opt(b), _opt(c), _opt(sink), int(n), int(slots),
+                                              int(run), int(max_groups_per_unit), _stream(stream))
     if rc != SPLC_OK:
         raise SparseLoCoError(rc, "sparseloco_stream_probe")
 

@@ -83,3 +83,10 @@ def test_stream_probe_arguments():
     assert L.sparseloco_stream_probe(B.SPLC_STREAM_WRITE, None, None, 4096, None, 100, None) == B.SPLC_EINVAL   # n % 4096
     assert L.sparseloco_stream_probe(B.SPLC_STREAM_WRITE, None, None, 4100, None, 4096, None) == B.SPLC_EALIGN
     assert L.sparseloco_stream_probe(B.SPLC_STREAM_WRITE, None, None, 4096, None, 0, None) == B.SPLC_OK
+    shaped = L.sparseloco_stream_probe_shaped
+    assert shaped(B.SPLC_STREAM_WRITE, None, None, 4096, None, 4096 * 8, 2, 0, 0, None) == B.SPLC_EINVAL     # slots: 1 or 4
+    assert shaped(B.SPLC_STREAM_WRITE, None, None, 4096, None, 4096 * 8, 4, 0, 9, None) == B.SPLC_EINVAL     # groups per unit
+    assert shaped(B.SPLC_STREAM_WRITE, None, None, 4096, None, 4096 * 8, 4, -1, 0, None) == B.SPLC_EINVAL
+    assert shaped(B.SPLC_STREAM_WRITE, None, None, 4096, None, 4096 * 12, 4, 1, 0, None) == B.SPLC_EINVAL    # 12 groups: no whole runs
+    assert shaped(B.SPLC_STREAM_WRITE, None, None, 4096, None, 4096 * 16, 1, 16, 0, None) == B.SPLC_EINVAL   # 64 groups < 8 * 16
+    assert shaped(B.SPLC_STREAM_WRITE, None, None, 4096, None, 0, 1, 16, 1, None) == B.SPLC_OK

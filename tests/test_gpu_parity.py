@@ -486,6 +486,24 @@ def test_runs_on_a_side_stream():
     parity.compare(got, want, "side stream")
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(slots=1), dict(run=16), dict(slots=1, run=4), dict(max_groups_per_unit=1),
+                                dict(run=2, max_groups_per_unit=3)], ids=str)
+def test_stream_probe_shapes_cover_every_element(kw):
+    """The measurement aid touches every element exactly once whatever the launch shape: the write pattern fills
+    the whole array, the compress pattern leaves (a - b) + c everywhere."""
+    n = 4096 * 8 * 16 * 3
+    g = torch.Generator(device="cuda").manual_seed(12)
+    a, b, c = (torch.randn(n, generator=g, device="cuda") for _ in range(3))
+    sink = torch.zeros(1, device="cuda")
+    want = (a - b) + c
+    B.sparseloco_stream_probe(B.SPLC_STREAM_R3W1, a, b, c, sink, **kw)
+    assert torch.equal(c, want)
+    B.sparseloco_stream_probe(B.SPLC_STREAM_WRITE, a, b, c, sink, **kw)
+    assert torch.equal(c, torch.tensor([1.0, 2.0, 3.0, 4.0], device="cuda").repeat(n // 4))
+    B.sparseloco_stream_probe(B.SPLC_STREAM_COPY, a, b, c, sink, **kw)
+    assert torch.equal(c, a)
+
+
 def test_error_returns_do_not_launch():
     plan = B.Plan([4096, 10], 32)
     e = [torch.zeros(4096, device="cuda"), torch.zeros(10, device="cuda")]
