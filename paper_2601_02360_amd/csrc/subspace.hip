@@ -280,8 +280,13 @@ template <int MATH, int TM_, int TN_>
 struct GemmStaging;
 template <int TM_, int TN_>
 struct GemmStaging<MATH_F32, TM_, TN_> {
-    float a[2][TK][TM_ + 4];
-    float b[2][TK][TN_ + 4];
+    // Pitch of a tile staged "row of k" (A always, B when given as N x K): rows + 2.  The lanes that share a
+    // matrix row store k values TK / (lanes per row) apart, i.e. 8 (4) pitches apart for the 128 (64) row
+    // tile; with a pitch = 2 mod 8 these land 16 (8) banks apart and a store instruction is free of bank
+    // conflicts.  The operand reads (consecutive rows of one k per half wave) are conflict free at any pitch.
+    static constexpr int kPitchA = TM_ + 2, kPitchBRows = TN_ + 2;
+    float a[2][TK][kPitchA];
+    float b[2][TK][TN_ + 4];       // K x N tiles and the epilogue slab use this pitch; N x K tiles use kPitchBRows
 };
 template <int TM_, int TN_>
 struct GemmStaging<MATH_BF16X3, TM_, TN_> {
@@ -407,6 +412,14 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<MATH, TM_, TN_, Pro>())) 
                 *reinterpret_cast<vuint2*>(dst) = vuint2{pack_bf16(h[0][p], h[1][p]), pack_bf16(h[2][p], h[3][p])};
         }
     };
+    // fp32 B tile given as N x K: same memory as sm.b, pitch kPitchBRows
+    auto b_rows = [&](int buf, int k, int n) -> float& {
+        if constexpr (SPLIT) {
+            return *reinterpret_cast<float*>(&sm.b[0][0][0][0]);        // not used with split operands
+        } else {
+            return reinterpret_cast<float*>(&sm.b[buf][0][0])[k * GemmStaging<MATH, TM_, TN_>::kPitchBRows + n];
+        }
+    };
     auto stash = [&](int buf, Stage& q) {
         pro.template apply<AF>(q.a, q.t);
         if constexpr (SPLIT) {
@@ -417,7 +430,7 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<MATH, TM_, TN_, Pro>())) 
             for (int i = 0; i < AF; ++i) sm.a[buf][ak + i][ar] = q.a[i];
             if (B_NK) {
 #pragma unroll
-                for (int i = 0; i < BF; ++i) sm.b[buf][bkk + i][br] = q.b[i];
+                for (int i = 0; i < BF; ++i) b_rows(buf, bkk + i, br) = q.b[i];
             } else {
 #pragma unroll
                 for (int i = 0; i < BF; ++i) sm.b[buf][bk][bn + i] = q.b[i];
@@ -464,7 +477,10 @@ __global__ __launch_bounds__(kThreads, (gemm_min_waves<MATH, TM_, TN_, Pro>())) 
 #pragma unroll
             for (int i = 0; i < MI; ++i) fa[st][i] = sm.a[buf][kk + kq][wm * (32 * MI) + 32 * i + rc];
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) fb[st][j] = sm.b[buf][kk + kq][wn * (32 * NJ) + 32 * j + rc];
+            for (int j = 0; j < NJ; ++j) {
+                const int col = wn * (32 * NJ) + 32 * j + rc;
+                fb[st][j] = B_NK ? b_rows(buf, kk + kq, col) : sm.b[buf][kk + kq][col];
+            }
         };
         operands(0, 0);
 #pragma unroll
